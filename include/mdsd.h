@@ -100,12 +100,15 @@ typedef struct mdsd_result {
     int32_t* outcome;      /* device [B,N], required: accepted child slot or MDSD_* code       */
     int32_t* token;        /* device [B,N], required: the token this node emits (the accepted
                               child's token, else the residual / bonus sample)                 */
-    float* resid_mass;     /* device [B,N] or NULL: mass of the residual the node would resample
-                              from (SpecHub: sum_x p''(x); RRS: product-free mass of the last
-                              max(p - c q, 0); leaf: sum p).  Non-NULL disables early exit.    */
+    float* resid_mass;     /* device [B,N] or NULL: mass of the node's residual in units of p.
+                              SpecHub: sum_x p''(x) (= 1 - total acceptance, whatever the tokens);
+                              RRS/RRSw: mass of max(p - c q, 0) when the node returned, i.e. the
+                              probability mass the rejections so far left; leaf: sum p.
+                              Non-NULL disables SpecHub's early exit.                          */
     int32_t* flags;        /* device [B,N] or NULL: MDSD_FLAG_* bits                           */
-    float* resid_prob;     /* device [B,N,V] or NULL (diagnostic): the normalised distribution
-                              the node resamples from after rejecting all its drafts           */
+    float* resid_prob;     /* device [B,N,V] or NULL (diagnostic): SpecHub: norm(p''); RRS/RRSw:
+                              the target distribution as it stood when the node returned (after
+                              the rejections made so far); leaf: p                             */
     int32_t* accept_depth; /* device [B] or NULL: number of accepted draft tokens on the path  */
     int32_t* emitted;      /* device [B,depth] or NULL: emitted tokens, -1 padded; tokens per
                               step = accept_depth + 1 (Sec. 5.3 batch efficiency)              */

@@ -307,9 +307,10 @@ int orc_spechub_verify(const double* p, const double* q, int V, int a,
 /* draft distribution before x_i is zeroed, then x_i is zeroed and q   */
 /* renormalised.  A residual without mass (possible only when p <= q   */
 /* everywhere, where rejection has probability 0) leaves p unchanged.  */
-/* Outputs as above; P_out (optional, V) = the distribution the final  */
-/* "Return x ~ p" draws from after k rejections, whatever happened;    */
-/* mass_out (optional, k) = sum max(p - q, 0) found in each round.     */
+/* Outputs as above; P_out (optional, V) = the target distribution p   */
+/* as it stands when the procedure returns (after i rejections when    */
+/* x_{i+1} was accepted; the one "Return x ~ p" draws from otherwise); */
+/* mass_out (optional, k) = sum max(p - q, 0) of each rejected round.  */
 /* ------------------------------------------------------------------ */
 int orc_rrs_verify(const double* p, const double* q, int V, int k,
                    const int* x, const double* r, double u,
@@ -330,23 +331,20 @@ int orc_rrs_verify(const double* p, const double* q, int V, int k,
             outcome = ORC_OUTCOME_BAD_TOKEN;
             decided = 1;
         }
-    int exhausted = 0;
-    for (int i = 0; i < k; ++i) {
-        int xi = (flags & ORC_FLAG_BAD_TOKEN) ? 0 : x[i];
-        /* while the outcome is open, run the test; afterwards keep updating
-         * P so that P_out is the k-rejection residual in every case */
-        if (!decided && !exhausted && accept_test(r[i], Qc[xi], P[xi], &mg)) {
+    for (int i = 0; i < k && !decided; ++i) {
+        int xi = x[i];
+        if (accept_test(r[i], Qc[xi], P[xi], &mg)) {
             outcome = i;
             *token = xi;
             decided = 1;
+            break;
         }
-        if (exhausted) continue;
         double M = 0.0;
         for (int y = 0; y < V; ++y) M += dmax(P[y] - Qc[y], 0.0);
         if (mass_out) mass_out[i] = M;
         if (M > 0.0) {
             for (int y = 0; y < V; ++y) P[y] = dmax(P[y] - Qc[y], 0.0) / M;
-        } else if (!decided) {
+        } else {
             flags |= ORC_FLAG_ZERO_RESIDUAL;
         }
         if (without_replacement) {
@@ -356,8 +354,8 @@ int orc_rrs_verify(const double* p, const double* q, int V, int k,
             if (s > 0.0) {
                 for (int y = 0; y < V; ++y) Qc[y] /= s;
             } else { /* READING: nothing left to draft from -> go to the end */
-                if (!decided) flags |= ORC_FLAG_Q_EXHAUSTED;
-                exhausted = 1;
+                flags |= ORC_FLAG_Q_EXHAUSTED;
+                break;
             }
         }
     }
@@ -508,10 +506,15 @@ int orc_batch_verify(const orc_problem* pb, int method, const int32_t* tokens,
                     xi[i] = xt[i];
                     ri[i] = (double)ur[i];
                 }
+                double mass[16];
+                for (int i = 0; i < k; ++i) mass[i] = 1.0;
                 oc = orc_rrs_verify(p, q, V, k, xi, ri, (double)ur[k], method == 2,
-                                    &tok, &mg, &fl, res, NULL);
-                rm = 0.0;
-                for (int y = 0; y < V; ++y) rm += res[y];
+                                    &tok, &mg, &fl, res, mass);
+                /* mass of the unnormalised k-fold residual: the product of the
+                 * per-round masses (a round without mass changes nothing) */
+                rm = 1.0;
+                for (int i = 0; i < k; ++i)
+                    if (mass[i] > 0.0) rm *= mass[i];
             }
         }
         outcome[r] = oc;

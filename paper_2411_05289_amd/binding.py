@@ -1,0 +1,280 @@
+"""Thin Python binding of the C ABI in ``include/mdsd.h``.
+
+Argument marshalling only: torch supplies device memory and the HIP stream;
+every step of the method runs inside ``libmdsd.so``.  There is no fallback: if
+the library has not been built, or a tensor is not on the GPU, the call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmdsd.so")
+
+FP32, BF16 = 0, 1
+PROBS, LOGITS = 0, 1
+NONE, BAD_PAIR, BAD_TOKEN = -1, -2, -3
+FLAG_DEGENERATE_HUB, FLAG_ZERO_RESIDUAL, FLAG_Q_EXHAUSTED, FLAG_BAD_PAIR, FLAG_BAD_TOKEN = 1, 2, 4, 8, 16
+
+EXPORTS = ("mdsd_workspace_bytes", "spechub_draft", "spechub_verify", "rrs_draft", "rrsw_draft",
+           "rrs_verify", "rrsw_verify", "mdsd_tree_walk", "mdsd_philox_uniform", "mdsd_strerror",
+           "mdsd_version")
+
+
+class MdsdError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__("%s: %s (%d)" % (where, strerror(code), code))
+
+
+class _Problem(C.Structure):
+    _fields_ = [
+        ("target", C.c_void_p), ("draft", C.c_void_p),
+        ("ld_t", C.c_int64), ("ld_d", C.c_int64),
+        ("dtype", C.c_int32), ("kind", C.c_int32),
+        ("temp_target", C.c_float), ("temp_draft", C.c_float),
+        ("B", C.c_int32), ("N", C.c_int32), ("V", C.c_int32),
+        ("k", C.c_int32), ("depth", C.c_int32),
+        ("first_child", C.c_void_p),
+    ]
+
+
+class _Result(C.Structure):
+    _fields_ = [
+        ("outcome", C.c_void_p), ("token", C.c_void_p), ("resid_mass", C.c_void_p),
+        ("flags", C.c_void_p), ("resid_prob", C.c_void_p), ("accept_depth", C.c_void_p),
+        ("emitted", C.c_void_p),
+    ]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded HIP library.  Raises if it is missing: there is no CPU path."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libmdsd.so is not built (run `python -m paper_2411_05289_amd.build`); "
+                "this package has no fallback path")
+        L = C.CDLL(LIB_PATH)
+        L.mdsd_workspace_bytes.restype = C.c_size_t
+        L.mdsd_workspace_bytes.argtypes = [C.c_void_p]
+        L.mdsd_strerror.restype = C.c_char_p
+        L.mdsd_strerror.argtypes = [C.c_int]
+        L.mdsd_version.restype = C.c_int
+        dv = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.spechub_draft.argtypes = dv
+        L.rrs_draft.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.rrsw_draft.argtypes = L.rrs_draft.argtypes
+        vv = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        for f in (L.spechub_verify, L.rrs_verify, L.rrsw_verify):
+            f.argtypes = vv
+            f.restype = C.c_int
+        for f in (L.spechub_draft, L.rrs_draft, L.rrsw_draft):
+            f.restype = C.c_int
+        L.mdsd_tree_walk.argtypes = [C.c_void_p] * 6
+        L.mdsd_tree_walk.restype = C.c_int
+        L.mdsd_philox_uniform.argtypes = [C.c_uint64, C.c_uint32, C.c_int64, C.c_int32, C.c_void_p,
+                                          C.c_void_p, C.c_void_p]
+        L.mdsd_philox_uniform.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().mdsd_strerror(code).decode()
+
+
+def version() -> int:
+    return lib().mdsd_version()
+
+
+@dataclass
+class Problem:
+    """Rows of one batch of token trees (device tensors) and the tree shape."""
+    target: Optional[torch.Tensor]   # [B,N,V] float32 or bfloat16; None for draft-only use
+    draft: torch.Tensor              # [B,N,V]
+    kind: int                        # PROBS | LOGITS
+    k: int
+    depth: int
+    temp_target: float = 1.0
+    temp_draft: float = 1.0
+    first_child: Optional[torch.Tensor] = None  # [N] int32 on device, or None
+
+    @staticmethod
+    def from_workload(wl) -> "Problem":
+        return Problem(wl.target, wl.draft, LOGITS if wl.kind == "logits" else PROBS, wl.k, wl.depth,
+                       wl.temp_target, wl.temp_draft, wl.first_child)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _check_rows(t: torch.Tensor, name: str):
+    if not t.is_cuda:
+        raise ValueError("%s must live on the GPU" % name)
+    if t.dim() != 3 or t.stride(2) != 1 or t.stride(0) != t.shape[1] * t.stride(1):
+        raise ValueError("%s must be [B,N,V] with unit stride in V and B-major rows" % name)
+    if t.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("%s must be float32 or bfloat16" % name)
+
+
+def _check_dev(t: torch.Tensor, name: str, dtype, shape):
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous() or tuple(t.shape) != tuple(shape):
+        raise ValueError("%s must be a contiguous %s GPU tensor of shape %s" % (name, dtype, tuple(shape)))
+
+
+def _c_problem(pb: Problem) -> _Problem:
+    _check_rows(pb.draft, "draft")
+    B, N, V = pb.draft.shape
+    cp = _Problem()
+    if pb.target is not None:
+        _check_rows(pb.target, "target")
+        if pb.target.shape != pb.draft.shape or pb.target.dtype != pb.draft.dtype:
+            raise ValueError("target and draft must agree in shape and dtype")
+        cp.target = pb.target.data_ptr()
+        cp.ld_t = pb.target.stride(1)
+    else:
+        cp.target = None
+        cp.ld_t = pb.draft.stride(1)
+    cp.draft = pb.draft.data_ptr()
+    cp.ld_d = pb.draft.stride(1)
+    cp.dtype = FP32 if pb.draft.dtype == torch.float32 else BF16
+    cp.kind = pb.kind
+    cp.temp_target, cp.temp_draft = pb.temp_target, pb.temp_draft
+    cp.B, cp.N, cp.V, cp.k, cp.depth = B, N, V, pb.k, pb.depth
+    if pb.first_child is not None:
+        _check_dev(pb.first_child, "first_child", torch.int32, (N,))
+        cp.first_child = pb.first_child.data_ptr()
+    else:
+        cp.first_child = None
+    return cp
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def workspace_bytes(pb: Problem) -> int:
+    cp = _c_problem(pb)
+    return int(lib().mdsd_workspace_bytes(C.byref(cp)))
+
+
+def _draft(fn_name, pb: Problem, u: torch.Tensor, out, with_hub: bool):
+    cp = _c_problem(pb)
+    B, N, _ = pb.draft.shape
+    dev = pb.draft.device
+    _check_dev(u, "u", torch.float32, (B, N, pb.k))
+    out = {} if out is None else out
+    if "tokens" not in out:
+        out["tokens"] = torch.empty((B, N), dtype=torch.int32, device=dev)
+    if "flags" not in out:
+        out["flags"] = torch.empty((B, N), dtype=torch.int32, device=dev)
+    if with_hub and "hub" not in out:
+        out["hub"] = torch.empty((B, N), dtype=torch.int32, device=dev)
+    _check_dev(out["tokens"], "tokens", torch.int32, (B, N))
+    fn = getattr(lib(), fn_name)
+    if with_hub:
+        rc = fn(C.byref(cp), _ptr(u), _ptr(out["tokens"]), _ptr(out["hub"]), _ptr(out["flags"]), None, 0, _stream())
+    else:
+        rc = fn(C.byref(cp), _ptr(u), _ptr(out["tokens"]), _ptr(out["flags"]), None, 0, _stream())
+    if rc != 0:
+        raise MdsdError(rc, fn_name)
+    return out
+
+
+def spechub_draft(pb: Problem, u: torch.Tensor, out=None):
+    """Sample the (x1, x2) ~ Q pair of every internal node.  -> dict(tokens, hub, flags)."""
+    return _draft("spechub_draft", pb, u, out, True)
+
+
+def rrs_draft(pb: Problem, u: torch.Tensor, out=None):
+    return _draft("rrs_draft", pb, u, out, False)
+
+
+def rrsw_draft(pb: Problem, u: torch.Tensor, out=None):
+    return _draft("rrsw_draft", pb, u, out, False)
+
+
+def alloc_result(pb: Problem, *, resid_mass=False, flags=True, resid_prob=False, walk=True):
+    """Output tensors for a verify call (so that a timed loop allocates nothing)."""
+    B, N, V = pb.draft.shape
+    dev = pb.draft.device
+    out = dict(outcome=torch.empty((B, N), dtype=torch.int32, device=dev),
+               token=torch.empty((B, N), dtype=torch.int32, device=dev))
+    if resid_mass:
+        out["resid_mass"] = torch.empty((B, N), dtype=torch.float32, device=dev)
+    if flags:
+        out["flags"] = torch.empty((B, N), dtype=torch.int32, device=dev)
+    if resid_prob:
+        out["resid_prob"] = torch.empty((B, N, V), dtype=torch.float32, device=dev)
+    if walk:
+        out["accept_depth"] = torch.empty((B,), dtype=torch.int32, device=dev)
+        out["emitted"] = torch.empty((B, pb.depth), dtype=torch.int32, device=dev)
+    return out
+
+
+def _verify(fn_name, pb: Problem, tokens: torch.Tensor, u: torch.Tensor, out, **want):
+    cp = _c_problem(pb)
+    if pb.target is None:
+        raise ValueError("verify needs target rows")
+    B, N, _ = pb.draft.shape
+    _check_dev(tokens, "tokens", torch.int32, (B, N))
+    _check_dev(u, "u", torch.float32, (B, N, pb.k + 1))
+    if out is None:
+        out = alloc_result(pb, **want)
+    res = _Result()
+    for name in ("outcome", "token", "resid_mass", "flags", "resid_prob", "accept_depth", "emitted"):
+        t = out.get(name)
+        if t is not None and not (t.is_cuda and t.is_contiguous()):
+            raise ValueError("output %s must be a contiguous GPU tensor" % name)
+        setattr(res, name, None if t is None else t.data_ptr())
+    rc = getattr(lib(), fn_name)(C.byref(cp), _ptr(tokens), _ptr(u), C.byref(res), None, 0, _stream())
+    if rc != 0:
+        raise MdsdError(rc, fn_name)
+    return out
+
+
+def spechub_verify(pb: Problem, tokens, u, out=None, **want):
+    """Alg. 3 on every node plus the tree walk.  -> dict(outcome, token, [resid_mass],
+    [flags], [resid_prob], [accept_depth, emitted])."""
+    return _verify("spechub_verify", pb, tokens, u, out, **want)
+
+
+def rrs_verify(pb: Problem, tokens, u, out=None, **want):
+    return _verify("rrs_verify", pb, tokens, u, out, **want)
+
+
+def rrsw_verify(pb: Problem, tokens, u, out=None, **want):
+    return _verify("rrsw_verify", pb, tokens, u, out, **want)
+
+
+def tree_walk(pb: Problem, outcome, token):
+    B, N, _ = pb.draft.shape
+    cp = _c_problem(pb)
+    dev = pb.draft.device
+    ad = torch.empty((B,), dtype=torch.int32, device=dev)
+    em = torch.empty((B, pb.depth), dtype=torch.int32, device=dev)
+    rc = lib().mdsd_tree_walk(C.byref(cp), _ptr(outcome), _ptr(token), _ptr(ad), _ptr(em), _stream())
+    if rc != 0:
+        raise MdsdError(rc, "mdsd_tree_walk")
+    return ad, em
+
+
+def philox_uniform(seed: int, stream_id: int, rows: int, slots: int, device="cuda", want_words=False):
+    """[rows, slots] float32 uniforms in [0,1) from Philox4x32-10 (and the raw words)."""
+    out = torch.empty((rows, slots), dtype=torch.float32, device=device)
+    words = torch.empty((rows, slots), dtype=torch.int32, device=device) if want_words else None
+    rc = lib().mdsd_philox_uniform(C.c_uint64(seed), C.c_uint32(stream_id), C.c_int64(rows),
+                                   C.c_int32(slots), _ptr(out), _ptr(words), _stream())
+    if rc != 0:
+        raise MdsdError(rc, "mdsd_philox_uniform")
+    return (out, words) if want_words else out

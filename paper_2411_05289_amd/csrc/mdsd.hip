@@ -1,0 +1,1052 @@
+// HIP kernels and C ABI of the sampling-verification library (gfx950).
+//
+// One workgroup of 256 threads owns one tree node: it scans the node's target
+// row (and, for a node with children, its draft row) a few times, each scan a
+// sequence of fully coalesced 16-byte loads, and decides the node's outcome.
+// The passes of one node:
+//   max     max of the stored logits (and the hub = argmax of the draft row)
+//   norm    softmax normalisers (sum of 2^((l - max) * log2e / T))
+//   resid   the vocabulary-wide residual sums of the method, with one partial
+//           sum per slab left in LDS
+//   draw    inverse-CDF search over the slab sums, then inside one slab
+// Scalar look-ups of p(x), q(x) at the draft tokens sit between them.
+#include <hip/hip_runtime.h>
+#include <limits.h>
+#include <stdint.h>
+
+#include "mdsd.h"
+#include "scan_core.h"
+
+namespace mdsd {
+
+enum Method { kSpecHub = 0, kRRS = 1, kRRSw = 2 };
+
+struct Params {
+    const void* target;
+    const void* draft;
+    int64_t ld_t, ld_d;
+    float temp_target, temp_draft;
+    int B, N, V, k, depth, n_internal;
+    const int32_t* first_child;
+    const int32_t* tokens;
+    const float* u;
+    int32_t* outcome;
+    int32_t* token;
+    float* resid_mass;
+    int32_t* flags;
+    float* resid_prob;
+    // draft kernels
+    int32_t* tokens_out;
+    int32_t* hub_out;
+};
+
+struct Shared {
+    BlockScratch<kWaves> red;
+    float slab_w[kMaxSlabs];
+};
+
+// Node of this workgroup.  Complete trees: nodes with children first (they
+// scan two rows), leaves after, so the long workgroups start early.
+struct NodeId {
+    int b, n, c0;
+    int64_t row;
+};
+
+__device__ __forceinline__ NodeId node_of_block(const Params& P)
+{
+    NodeId id;
+    int w = blockIdx.x;
+    if (P.first_child == nullptr) {
+        const int total_int = P.B * P.n_internal;
+        if (w < total_int) {
+            id.b = w / P.n_internal;
+            id.n = w - id.b * P.n_internal;
+            id.c0 = P.k * id.n + 1;
+        } else {
+            w -= total_int;
+            const int n_leaf = P.N - P.n_internal;
+            id.b = w / n_leaf;
+            id.n = P.n_internal + (w - id.b * n_leaf);
+            id.c0 = -1;
+        }
+    } else {
+        id.b = w / P.N;
+        id.n = w - id.b * P.N;
+        id.c0 = P.first_child[id.n];
+        // an entry that leaves no room for k children is treated as a leaf
+        if (id.c0 < 1 || id.c0 + P.k > P.N) id.c0 = -1;
+    }
+    id.row = (int64_t)id.b * P.N + id.n;
+    return id;
+}
+
+// ---------------------------------------------------------------- passes
+// max of the stored values of one row
+template <int DT>
+__device__ __forceinline__ float lane_max1(const RowView& r)
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    float m = -__builtin_inff();
+    slab_loop1<DT>(r, -__builtin_inff(), [&](int, int, const float(&a)[E]) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) m = fmaxf(m, a[e]);
+    });
+    return m;
+}
+
+// max of the stored values and the lowest index where this lane saw it
+template <int DT>
+__device__ __forceinline__ void lane_argmax1(const RowView& r, float& m, int& idx)
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    m = -__builtin_inff();
+    idx = INT_MAX;
+    slab_loop1<DT>(r, -__builtin_inff(), [&](int, int chunk, const float(&a)[E]) {
+#pragma unroll
+        for (int e = 0; e < E; ++e)
+            if (a[e] > m) {
+                m = a[e];
+                idx = chunk * E + e;
+            }
+    });
+}
+
+// hub = lowest index among the maxima of the stored draft row (virtual index)
+template <int DT>
+__device__ __forceinline__ int block_argmax(const RowView& r, float& m_out, Shared& sh, int& phase)
+{
+    float m;
+    int idx;
+    lane_argmax1<DT>(r, m, idx);
+    float mm[1] = {m};
+    block_max<kWaves, 1>(mm, sh.red, phase);
+    m_out = mm[0];
+    const int a = block_min_index<kWaves>(m == mm[0] ? idx : INT_MAX, sh.red, phase);
+    return a == INT_MAX ? r.head : a;  // a row of NaNs has no maximum: stay in bounds
+}
+
+// sum of the weights of one row with one slab sum per slab left in LDS;
+// elements whose virtual index is in excl[0..n_excl) count as 0
+template <int DT, bool LOGITS>
+__device__ __forceinline__ void pass_weights_to_slabs(const RowView& r, ToWeight<LOGITS> cv,
+                                                      const int* excl, int n_excl, float* slab_w)
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    slab_loop1<DT>(r, ToWeight<LOGITS>::fill(), [&](int s, int chunk, const float(&a)[E]) {
+        float w[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) w[e] = cv(a[e]);
+        for (int j = 0; j < n_excl; ++j)
+            if (excl[j] / (64 * E) == s) {
+#pragma unroll
+                for (int e = 0; e < E; ++e)
+                    if (chunk * E + e == excl[j]) w[e] = 0.f;
+            }
+        store_slab_sum(slab_w, s, chunk_sum<E>(w));
+    });
+}
+
+// this lane's chunk of slab s of the same weights (for the draw inside a slab)
+template <int DT, bool LOGITS>
+__device__ __forceinline__ void chunk_weights(const RowView& r, ToWeight<LOGITS> cv,
+                                              const int* excl, int n_excl, int s,
+                                              float (&w)[Elem<DT>::kPerChunk])
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    const int chunk = s * 64 + (threadIdx.x & 63);
+    float a[E];
+    load_chunk<DT>(r, chunk, ToWeight<LOGITS>::fill(), a);
+#pragma unroll
+    for (int e = 0; e < E; ++e) w[e] = cv(a[e]);
+    for (int j = 0; j < n_excl; ++j) {
+#pragma unroll
+        for (int e = 0; e < E; ++e)
+            if (chunk * E + e == excl[j]) w[e] = 0.f;
+    }
+}
+
+// Draw from the weights of one row (slab sums already in LDS and visible).
+template <int DT, bool LOGITS>
+__device__ __forceinline__ int draw_from_row(const RowView& r, ToWeight<LOGITS> cv,
+                                             const int* excl, int n_excl, const float* slab_w,
+                                             float u, float& W)
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    auto sv = [&](int i) { return slab_w[i]; };
+    W = slab_total(r.nslab, sv);
+    return icdf_slabs<E>(r.nslab, u, W, sv,
+                         [&](int s, float(&w)[E]) { chunk_weights<DT, LOGITS>(r, cv, excl, n_excl, s, w); });
+}
+
+// ---------------------------------------------------------------- SpecHub element arithmetic
+// App. B.2 for one token y != a, from unnormalised weights ep, eq:
+//   P = ep/Zp, Q = eq/Zq, p' = max(P - Q, 0), Q'(y,a) = max(Q - P, 0),
+//   t = c Q - p'  ->  Q'(a,y) = max(t, 0),  p''(y) = max(-t, 0).
+struct HubScal {
+    float iZp, iZq, c;
+};
+
+__device__ __forceinline__ void spechub_terms(float ep, float eq, const HubScal& h, float& q_xa_res,
+                                              float& q_ax_res, float& w)
+{
+    const float Pn = ep * h.iZp;
+    const float Qn = eq * h.iZq;
+    const float d = Pn - Qn;
+    q_xa_res = fmaxf(-d, 0.f);
+    const float t = fmaf(h.c, Qn, -fmaxf(d, 0.f));
+    q_ax_res = fmaxf(t, 0.f);
+    w = fmaxf(-t, 0.f);
+}
+
+template <int DT, bool LOGITS>
+__device__ __forceinline__ void spechub_chunk_w(const RowView& rp, const RowView& rq,
+                                                ToWeight<LOGITS> cp, ToWeight<LOGITS> cq,
+                                                const HubScal& h, int a_virt, int s,
+                                                float (&w)[Elem<DT>::kPerChunk])
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    const int chunk = s * 64 + (threadIdx.x & 63);
+    float a[E], b[E];
+    load_chunk<DT>(rp, chunk, ToWeight<LOGITS>::fill(), a);
+    load_chunk<DT>(rq, chunk, ToWeight<LOGITS>::fill(), b);
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        float ep = cp(a[e]), eq = cq(b[e]);
+        if (chunk * E + e == a_virt) ep = eq = 0.f;
+        float s2, s1;
+        spechub_terms(ep, eq, h, s2, s1, w[e]);
+    }
+}
+
+// RRS residual weight for one token: max(p - c q, 0), c folded with 1/Zq
+__device__ __forceinline__ float rrs_term(float ep, float eq, float iZp, float c_iZq)
+{
+    return fmaxf(fmaf(-c_iZq, eq, ep * iZp), 0.f);
+}
+
+template <int DT, bool LOGITS>
+__device__ __forceinline__ void rrs_chunk_w(const RowView& rp, const RowView& rq,
+                                            ToWeight<LOGITS> cp, ToWeight<LOGITS> cq, float iZp,
+                                            float c_iZq, const int* excl, int n_excl, int s,
+                                            float (&w)[Elem<DT>::kPerChunk])
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    const int chunk = s * 64 + (threadIdx.x & 63);
+    float a[E], b[E];
+    load_chunk<DT>(rp, chunk, ToWeight<LOGITS>::fill(), a);
+    load_chunk<DT>(rq, chunk, ToWeight<LOGITS>::fill(), b);
+#pragma unroll
+    for (int e = 0; e < E; ++e) w[e] = rrs_term(cp(a[e]), cq(b[e]), iZp, c_iZq);
+    for (int j = 0; j < n_excl; ++j) {
+#pragma unroll
+        for (int e = 0; e < E; ++e)
+            if (chunk * E + e == excl[j]) w[e] = 0.f;
+    }
+}
+
+// write norm(w) of a whole row (diagnostic output)
+template <int DT, class ChunkW>
+__device__ __forceinline__ void write_resid_prob(float* out, const RowView& r, float W, ChunkW cw)
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float iW = W > 0.f ? 1.f / W : 0.f;
+    for (int s = wave; s < r.nslab; s += kWaves) {
+        float w[E];
+        cw(s, w);
+        const int v0 = (s * 64 + lane) * E;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const int v = v0 + e;
+            if (v >= r.head && v < r.nvirt) out[v - r.head] = w[e] * iW;
+        }
+    }
+}
+
+// ---------------------------------------------------------------- verify kernel
+template <int DT, bool LOGITS, int METHOD>
+__global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    using CV = ToWeight<LOGITS>;
+    __shared__ Shared sh;
+    int phase = 0;
+    const NodeId id = node_of_block(P);
+    const int k = P.k;
+    const float* ur = P.u + id.row * (k + 1);
+    const bool need_full = (P.resid_mass != nullptr) || (P.resid_prob != nullptr);
+    float* rprob = P.resid_prob ? P.resid_prob + id.row * (int64_t)P.V : nullptr;
+
+    const RowView rp = make_row<DT>(P.target, P.ld_t, id.row, P.V);
+    int outcome = MDSD_NONE, token = -1, flags = 0;
+    float rmass = 0.f;
+
+    if (id.c0 < 0) {
+        // ---- leaf: the k = 0 case of Alg. 1, token ~ p
+        CV cp{0.f, 0.f};
+        if constexpr (LOGITS) {
+            float mm[1] = {lane_max1<DT>(rp)};
+            block_max<kWaves, 1>(mm, sh.red, phase);
+            cp.s = kLog2e / P.temp_target;
+            cp.ms = mm[0] * cp.s;
+        }
+        pass_weights_to_slabs<DT, LOGITS>(rp, cp, nullptr, 0, sh.slab_w);
+        __syncthreads();
+        float W;
+        const int v = draw_from_row<DT, LOGITS>(rp, cp, nullptr, 0, sh.slab_w, ur[k], W);
+        token = v < 0 ? -1 : v - rp.head;
+        if (v < 0) flags |= MDSD_FLAG_ZERO_RESIDUAL;
+        rmass = LOGITS ? 1.f : W;
+        if (rprob)
+            write_resid_prob<DT>(rprob, rp, W, [&](int s, float(&w)[E]) {
+                chunk_weights<DT, LOGITS>(rp, cp, nullptr, 0, s, w);
+            });
+    } else {
+        const RowView rq = make_row<DT>(P.draft, P.ld_d, id.row, P.V);
+        const int32_t* xt = P.tokens + (int64_t)id.b * P.N + id.c0;
+        CV cp{0.f, 0.f}, cq{0.f, 0.f};
+
+        if constexpr (METHOD == kSpecHub) {
+            // ---- hub and softmax maxima
+            float mq;
+            const int a_virt = block_argmax<DT>(rq, mq, sh, phase);
+            const int a = a_virt - rq.head;
+            if constexpr (LOGITS) {
+                float mm[1] = {lane_max1<DT>(rp)};
+                block_max<kWaves, 1>(mm, sh.red, phase);
+                cp.s = kLog2e / P.temp_target;
+                cp.ms = mm[0] * cp.s;
+                cq.s = kLog2e / P.temp_draft;
+                cq.ms = mq * cq.s;
+            }
+            // ---- normalisers: Zp (logits only) and D-part Zq' = sum_{y != a} eq
+            float z[2] = {0.f, 0.f};
+            slab_loop2<DT>(rp, rq, CV::fill(), [&](int, int chunk, const float(&pa)[E], const float(&qa)[E]) {
+                float wp[E], wq[E];
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    wp[e] = cp(pa[e]);
+                    wq[e] = cq(qa[e]);
+                    if (chunk * E + e == a_virt) wq[e] = 0.f;
+                }
+                z[0] += chunk_sum<E>(wp);
+                z[1] += chunk_sum<E>(wq);
+            });
+            block_sum<kWaves, 2>(z, sh.red, phase);
+            const float ea_q = cq(load_elem<DT>(rq, a));
+            const float ea_p = cp(load_elem<DT>(rp, a));
+            const float Zq_rest = z[1];
+            HubScal h;
+            h.iZp = LOGITS ? 1.f / z[0] : 1.f;
+            h.iZq = LOGITS ? 1.f / (Zq_rest + ea_q) : 1.f;
+            h.c = ea_q / Zq_rest;  // q(a) / (1 - q(a)); unused when Zq_rest == 0
+            const float pa = ea_p * h.iZp;
+            const float qa = ea_q * h.iZq;
+
+            const int x1 = xt[0], x2 = xt[1];
+            bool decided = false, degenerate = false;
+            int hub_slot = -1;  // slot of the hub token in the pair
+            if (x1 < 0 || x1 >= P.V || x2 < 0 || x2 >= P.V) {
+                flags |= MDSD_FLAG_BAD_TOKEN;
+                outcome = MDSD_BAD_TOKEN;
+                decided = true;
+            } else if (!(Zq_rest > 0.f)) {
+                degenerate = true;
+                flags |= MDSD_FLAG_DEGENERATE_HUB;
+                if (x1 != a || x2 != a) {
+                    flags |= MDSD_FLAG_BAD_PAIR;
+                    outcome = MDSD_BAD_PAIR;
+                    decided = true;
+                } else if (ur[0] * qa < pa) {
+                    outcome = 0;
+                    token = a;
+                    decided = true;
+                }
+            } else if (x2 == a && x1 != a) {
+                hub_slot = 1;
+                const float px = cp(load_elem<DT>(rp, x1)) * h.iZp;
+                const float qx = cq(load_elem<DT>(rq, x1)) * h.iZq;
+                if (ur[0] * qx < px) {  // pair (x, a): min(p(x)/Q(x,a), 1)
+                    outcome = 0;
+                    token = x1;
+                    decided = true;
+                }
+            } else if (x1 == a && x2 != a) {
+                hub_slot = 0;
+                const float px = cp(load_elem<DT>(rp, x2)) * h.iZp;
+                const float qx = cq(load_elem<DT>(rq, x2)) * h.iZq;
+                if (ur[0] * (h.c * qx) < fmaxf(px - qx, 0.f)) {  // pair (a, x): min(p'(x)/Q(a,x), 1)
+                    outcome = 1;
+                    token = x2;
+                    decided = true;
+                }
+            } else {
+                flags |= MDSD_FLAG_BAD_PAIR;
+                outcome = MDSD_BAD_PAIR;
+                decided = true;
+            }
+
+            if (!decided || need_full) {
+                if (degenerate) {
+                    // residual of the single-draft case: p with the hub removed
+                    pass_weights_to_slabs<DT, LOGITS>(rp, cp, &a_virt, 1, sh.slab_w);
+                    __syncthreads();
+                    float W;
+                    const int v = draw_from_row<DT, LOGITS>(rp, cp, &a_virt, 1, sh.slab_w, ur[2], W);
+                    rmass = W * h.iZp;
+                    if (!decided) {
+                        token = v < 0 ? -1 : v - rp.head;
+                        if (v < 0) flags |= MDSD_FLAG_ZERO_RESIDUAL;
+                    }
+                    if (rprob)
+                        write_resid_prob<DT>(rprob, rp, W, [&](int s, float(&w)[E]) {
+                            chunk_weights<DT, LOGITS>(rp, cp, &a_virt, 1, s, w);
+                        });
+                } else {
+                    // ---- residual sums: S_xa = sum Q'(.,a), S_ax = sum Q'(a,.), slab sums of p''
+                    float sacc[2] = {0.f, 0.f};
+                    slab_loop2<DT>(rp, rq, CV::fill(),
+                                   [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
+                        float t_xa[E], t_ax[E], w[E];
+#pragma unroll
+                        for (int e = 0; e < E; ++e) {
+                            float ep = cp(pa_[e]), eq = cq(qa_[e]);
+                            if (chunk * E + e == a_virt) ep = eq = 0.f;
+                            spechub_terms(ep, eq, h, t_xa[e], t_ax[e], w[e]);
+                        }
+                        sacc[0] += chunk_sum<E>(t_xa);
+                        sacc[1] += chunk_sum<E>(t_ax);
+                        store_slab_sum(sh.slab_w, s, chunk_sum<E>(w));
+                    });
+                    block_sum<kWaves, 2>(sacc, sh.red, phase);  // barrier: slab sums visible
+                    const float S_xa = sacc[0], S_ax = sacc[1];
+                    if (!decided) {
+                        if (hub_slot == 1) {  // pair (x, a): hub draws on what pairs (a,.) left
+                            const float pa1 = fmaxf(pa - S_ax, 0.f);
+                            if (ur[1] * S_xa < pa1) {
+                                outcome = 1;
+                                token = a;
+                                decided = true;
+                            }
+                        } else {  // pair (a, x)
+                            if (ur[1] * S_ax < pa) {
+                                outcome = 0;
+                                token = a;
+                                decided = true;
+                            }
+                        }
+                    }
+                    auto sv = [&](int i) { return sh.slab_w[i]; };
+                    auto cw = [&](int s, float(&w)[E]) {
+                        spechub_chunk_w<DT, LOGITS>(rp, rq, cp, cq, h, a_virt, s, w);
+                    };
+                    const float W = slab_total(rp.nslab, sv);
+                    rmass = W;
+                    bool wrote_prob = false;
+                    if (!decided) {
+                        int v = icdf_slabs<E>(rp.nslab, ur[2], W, sv, cw);
+                        if (v < 0) {
+                            // no residual mass: fall back to p itself
+                            flags |= MDSD_FLAG_ZERO_RESIDUAL;
+                            __syncthreads();
+                            pass_weights_to_slabs<DT, LOGITS>(rp, cp, nullptr, 0, sh.slab_w);
+                            __syncthreads();
+                            float Wp;
+                            v = draw_from_row<DT, LOGITS>(rp, cp, nullptr, 0, sh.slab_w, ur[2], Wp);
+                            if (rprob) {
+                                write_resid_prob<DT>(rprob, rp, Wp, [&](int s, float(&w)[E]) {
+                                    chunk_weights<DT, LOGITS>(rp, cp, nullptr, 0, s, w);
+                                });
+                                wrote_prob = true;
+                            }
+                        }
+                        token = v < 0 ? -1 : v - rp.head;
+                    }
+                    if (rprob && !wrote_prob) write_resid_prob<DT>(rprob, rp, W, cw);
+                }
+            }
+        } else {
+            // ---- RRS / RRSw (Alg. 1).  State: residual U = max(p - c q, 0) with mass Wc.
+            constexpr bool WO = (METHOD == kRRSw);
+            int xs[MDSD_MAX_K];
+            bool bad = false;
+            for (int i = 0; i < k; ++i) {
+                xs[i] = xt[i];
+                if (xs[i] < 0 || xs[i] >= P.V) bad = true;
+            }
+            if (bad) {
+                flags |= MDSD_FLAG_BAD_TOKEN;
+                outcome = MDSD_BAD_TOKEN;
+            } else {
+                if constexpr (LOGITS) {
+                    float mm[2] = {lane_max1<DT>(rp), lane_max1<DT>(rq)};
+                    block_max<kWaves, 2>(mm, sh.red, phase);
+                    cp.s = kLog2e / P.temp_target;
+                    cp.ms = mm[0] * cp.s;
+                    cq.s = kLog2e / P.temp_draft;
+                    cq.ms = mm[1] * cq.s;
+                }
+                // exclusion list (virtual indices) and duplicate marks
+                int xv[MDSD_MAX_K];
+                bool dup[MDSD_MAX_K];
+                for (int i = 0; i < k; ++i) {
+                    xv[i] = xs[i] + rp.head;
+                    dup[i] = false;
+                    for (int j = 0; j < i; ++j) dup[i] = dup[i] || (xs[j] == xs[i]);
+                }
+                // normalisers; without replacement the draft sum leaves out every draft token,
+                // so that the mass remaining after i removals is a sum of positive terms
+                float z[2] = {0.f, 0.f};
+                slab_loop2<DT>(rp, rq, CV::fill(), [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
+                    float wp[E], wq[E];
+#pragma unroll
+                    for (int e = 0; e < E; ++e) {
+                        wp[e] = cp(pa_[e]);
+                        wq[e] = cq(qa_[e]);
+                    }
+                    if constexpr (WO) {
+                        for (int j = 0; j < k; ++j)
+                            if (xv[j] / (64 * E) == s) {
+#pragma unroll
+                                for (int e = 0; e < E; ++e)
+                                    if (chunk * E + e == xv[j]) wq[e] = 0.f;
+                            }
+                    }
+                    z[0] += chunk_sum<E>(wp);
+                    z[1] += chunk_sum<E>(wq);
+                });
+                block_sum<kWaves, 2>(z, sh.red, phase);
+                float eqx[MDSD_MAX_K], rem[MDSD_MAX_K + 1];
+                for (int i = 0; i < k; ++i) eqx[i] = cq(load_elem<DT>(rq, xs[i]));
+                // rem[i] = draft mass (unnormalised) left before round i
+                rem[k] = z[1];
+                for (int i = k - 1; i >= 0; --i) rem[i] = rem[i + 1] + ((WO && !dup[i]) ? eqx[i] : 0.f);
+                const float Zq = rem[0];
+                const float iZp = LOGITS ? 1.f / z[0] : 1.f;
+                const float iZq = LOGITS ? 1.f / Zq : 1.f;
+
+                float c = 0.f, Wc = 1.f;
+                float slab_c = -1.f;  // c of the slab sums in LDS (-1: none)
+                int slab_nx = -1;
+                bool decided = false, exhausted = false;
+                int n_rej = 0;  // tokens xs[0..n_rej) have been rejected
+                for (int i = 0; i < k && !exhausted; ++i) {
+                    const float px = cp(load_elem<DT>(rp, xs[i])) * iZp;
+                    const float qx = eqx[i] * iZq;
+                    // draft probability of x_i in this round and the factor rho that rescales q;
+                    // without replacement a repeated token has no mass left (Alg. 1, red lines)
+                    float Qi = qx, rho = 1.f;
+                    if (WO && i > 0) {
+                        Qi = dup[i] ? 0.f : eqx[i] / rem[i];
+                        rho = 1.f / (rem[i] * iZq);
+                    }
+                    bool seen = false;
+                    for (int j = 0; j < i; ++j) seen = seen || (xs[j] == xs[i]);
+                    const float Ux = seen ? 0.f : fmaxf(fmaf(-c, qx, px), 0.f);
+                    if (ur[i] * Qi * Wc < Ux) {  // Alg. 1 returns at the first acceptance
+                        outcome = i;
+                        token = xs[i];
+                        decided = true;
+                        break;
+                    }
+                    // reject: U <- max(p - (c + Wc rho) q, 0)
+                    const float c_new = fmaf(Wc, rho, c);
+                    n_rej = i + 1;
+                    if (i > 0) __syncthreads();  // earlier readers of slab_w are done
+                    const float c_iZq = c_new * iZq;
+                    slab_loop2<DT>(rp, rq, CV::fill(), [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
+                        float w[E];
+#pragma unroll
+                        for (int e = 0; e < E; ++e) w[e] = rrs_term(cp(pa_[e]), cq(qa_[e]), iZp, c_iZq);
+                        for (int j = 0; j < n_rej; ++j)
+                            if (xv[j] / (64 * E) == s) {
+#pragma unroll
+                                for (int e = 0; e < E; ++e)
+                                    if (chunk * E + e == xv[j]) w[e] = 0.f;
+                            }
+                        store_slab_sum(sh.slab_w, s, chunk_sum<E>(w));
+                    });
+                    __syncthreads();
+                    const float W_new = slab_total(rp.nslab, [&](int j) { return sh.slab_w[j]; });
+                    if (W_new > 0.f) {
+                        c = c_new;
+                        Wc = W_new;
+                        slab_c = c_new;
+                        slab_nx = n_rej;
+                    } else {
+                        flags |= MDSD_FLAG_ZERO_RESIDUAL;
+                        slab_c = -1.f;
+                    }
+                    if constexpr (WO) {
+                        if (!(rem[i + 1] > 0.f)) {
+                            flags |= MDSD_FLAG_Q_EXHAUSTED;
+                            exhausted = true;
+                        }
+                    }
+                }
+                if (!decided || need_full) {
+                    const float c_iZq = c * iZq;
+                    auto cw = [&](int s, float(&w)[E]) {
+                        rrs_chunk_w<DT, LOGITS>(rp, rq, cp, cq, iZp, c_iZq, xv, n_rej, s, w);
+                    };
+                    if (slab_c != c || slab_nx != n_rej) {
+                        // slab sums in LDS are not those of the current residual (k == 0 cannot
+                        // happen here; a round without mass can): rebuild them
+                        __syncthreads();
+                        for (int s = threadIdx.x >> 6; s < rp.nslab; s += kWaves) {
+                            float w[E];
+                            cw(s, w);
+                            store_slab_sum(sh.slab_w, s, chunk_sum<E>(w));
+                        }
+                        __syncthreads();
+                    }
+                    auto sv = [&](int j) { return sh.slab_w[j]; };
+                    const float W = slab_total(rp.nslab, sv);
+                    rmass = W;
+                    if (!decided) {
+                        const int v = icdf_slabs<E>(rp.nslab, ur[k], W, sv, cw);
+                        token = v < 0 ? -1 : v - rp.head;
+                        if (v < 0) flags |= MDSD_FLAG_ZERO_RESIDUAL;
+                    }
+                    if (rprob) write_resid_prob<DT>(rprob, rp, W, cw);
+                }
+            }
+        }
+    }
+
+    if (threadIdx.x == 0) {
+        P.outcome[id.row] = outcome;
+        P.token[id.row] = token;
+        if (P.resid_mass) P.resid_mass[id.row] = rmass;
+        if (P.flags) P.flags[id.row] = flags;
+    }
+}
+
+// ---------------------------------------------------------------- draft kernel
+template <int DT, bool LOGITS, int METHOD>
+__global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    using CV = ToWeight<LOGITS>;
+    __shared__ Shared sh;
+    int phase = 0;
+    // one workgroup per node; a leaf only records that it has no hub
+    const NodeId id = node_of_block(P);
+    const int b = id.b, n = id.n, c0 = id.c0;
+    const int64_t row = id.row;
+    if (n == 0 && threadIdx.x == 0) P.tokens_out[(int64_t)b * P.N] = -1;
+    if (c0 < 0) {
+        if (threadIdx.x == 0) {
+            if (P.hub_out) P.hub_out[row] = -1;
+            if (P.flags) P.flags[row] = 0;
+        }
+        return;
+    }
+    const int k = P.k;
+    const float* ur = P.u + row * k;
+    const RowView rq = make_row<DT>(P.draft, P.ld_d, row, P.V);
+    int32_t* xt = P.tokens_out + (int64_t)b * P.N + c0;
+    int flags = 0;
+
+    CV cq{0.f, 0.f};
+    float mq;
+    const int a_virt = block_argmax<DT>(rq, mq, sh, phase);
+    if constexpr (LOGITS) {
+        cq.s = kLog2e / P.temp_draft;
+        cq.ms = mq * cq.s;
+    }
+    pass_weights_to_slabs<DT, LOGITS>(rq, cq, nullptr, 0, sh.slab_w);
+    __syncthreads();
+
+    // slab sums with some tokens removed: only the slabs holding a removed token change,
+    // and those are recomputed with the tokens masked (never by subtraction)
+    int excl[MDSD_MAX_K];
+    int ov_slab[MDSD_MAX_K];
+    float ov_val[MDSD_MAX_K];
+    int n_excl = 0, n_ov = 0;
+    auto sv = [&](int i) {
+        float v = sh.slab_w[i];
+        for (int j = 0; j < n_ov; ++j)
+            if (ov_slab[j] == i) v = ov_val[j];
+        return v;
+    };
+    auto cw = [&](int s, float(&w)[E]) { chunk_weights<DT, LOGITS>(rq, cq, excl, n_excl, s, w); };
+    auto remove_token = [&](int v) {
+        excl[n_excl++] = v;
+        const int s = v / (64 * E);
+        float w[E];
+        cw(s, w);
+        const float t = wave_sum(chunk_sum<E>(w));
+        int j = 0;
+        while (j < n_ov && ov_slab[j] != s) ++j;
+        ov_slab[j] = s;
+        ov_val[j] = t;
+        if (j == n_ov) ++n_ov;
+    };
+
+    int out_tok[MDSD_MAX_K];
+    if constexpr (METHOD == kSpecHub) {
+        const float W = slab_total(rq.nslab, sv);
+        const int v = icdf_slabs<E>(rq.nslab, ur[0], W, sv, cw);
+        if (v != a_virt) {
+            out_tok[0] = v < 0 ? -1 : v - rq.head;
+            out_tok[1] = a_virt - rq.head;
+        } else {
+            remove_token(a_virt);
+            const float W2 = slab_total(rq.nslab, sv);
+            int v2 = icdf_slabs<E>(rq.nslab, ur[1], W2, sv, cw);
+            if (v2 < 0) {
+                v2 = a_virt;
+                flags |= MDSD_FLAG_DEGENERATE_HUB;
+            }
+            out_tok[0] = a_virt - rq.head;
+            out_tok[1] = v2 - rq.head;
+        }
+    } else {
+        int prev = rq.head;
+        for (int i = 0; i < k; ++i) {
+            const float W = slab_total(rq.nslab, sv);
+            int v = icdf_slabs<E>(rq.nslab, ur[i], W, sv, cw);
+            if (v < 0) {
+                v = prev;
+                flags |= MDSD_FLAG_Q_EXHAUSTED;
+            } else if (METHOD == kRRSw) {
+                remove_token(v);
+            }
+            prev = v;
+            out_tok[i] = v - rq.head;
+        }
+    }
+    if (threadIdx.x == 0) {
+        for (int i = 0; i < k; ++i) xt[i] = out_tok[i];
+        if (P.hub_out) P.hub_out[row] = (METHOD == kSpecHub) ? a_virt - rq.head : -1;
+        if (P.flags) P.flags[row] = flags;
+    }
+}
+
+// ---------------------------------------------------------------- tree walk
+__global__ void tree_walk_kernel(const int32_t* outcome, const int32_t* token, int B, int N, int k,
+                                 int depth, const int32_t* first_child, int32_t* accept_depth,
+                                 int32_t* emitted)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const int32_t* oc = outcome + (int64_t)b * N;
+    const int32_t* tk = token + (int64_t)b * N;
+    int32_t* em = emitted + (int64_t)b * depth;
+    for (int i = 0; i < depth; ++i) em[i] = -1;
+    int n = 0, d = 0;
+    for (;;) {
+        if (d < depth) em[d] = tk[n];
+        int c0;
+        if (first_child) {
+            c0 = first_child[n];
+        } else {
+            const int64_t c = (int64_t)k * n + 1;
+            c0 = (c + k <= N) ? (int)c : -1;
+        }
+        const int o = oc[n];
+        if (c0 < 0 || o < 0 || o >= k || d + 1 >= depth) break;
+        n = c0 + o;
+        if (n >= N) break;
+        ++d;
+    }
+    accept_depth[b] = d;
+}
+
+// ---------------------------------------------------------------- Philox4x32-10
+// Salmon, Moraes, Dror, Shaw, SC'11: ten rounds of two 32x32->64 multiplies,
+// swap and xor with the key; the key advances by the two Weyl constants.
+__global__ void philox_uniform_kernel(uint32_t k0, uint32_t k1, uint32_t stream_id, int64_t rows,
+                                      int slots, float* out, uint32_t* words)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int blocks_per_row = (slots + 3) >> 2;
+    if (i >= rows * blocks_per_row) return;
+    const int64_t row = i / blocks_per_row;
+    const int blk = (int)(i - row * blocks_per_row);
+    uint32_t c0 = (uint32_t)row, c1 = (uint32_t)((uint64_t)row >> 32), c2 = (uint32_t)blk, c3 = stream_id;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
+        const uint32_t h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
+        const uint32_t n0 = h1 ^ c1 ^ k0, n2 = h0 ^ c3 ^ k1;
+        c0 = n0;
+        c1 = l1;
+        c2 = n2;
+        c3 = l0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    const uint32_t w[4] = {c0, c1, c2, c3};
+    for (int j = 0; j < 4; ++j) {
+        const int s = blk * 4 + j;
+        if (s < slots) {
+            if (out) out[row * slots + s] = (float)(w[j] >> 8) * (1.0f / 16777216.0f);
+            if (words) words[row * slots + s] = w[j];
+        }
+    }
+}
+
+// ---------------------------------------------------------------- host side
+static int complete_tree_nodes(int k, int depth, int64_t* n_internal)
+{
+    int64_t n = 0, level = 1, internal = 0;
+    for (int d = 0; d < depth; ++d) {
+        if (d == depth - 1) internal = n;
+        n += level;
+        level *= k;
+        if (n > INT_MAX) return -1;
+    }
+    *n_internal = internal;
+    return (int)n;
+}
+
+static int validate(const mdsd_problem* pb, int method, bool need_target, Params* P)
+{
+    if (!pb) return MDSD_E_NULL;
+    if (!pb->draft || (need_target && !pb->target)) return MDSD_E_NULL;
+    if (pb->dtype != MDSD_FP32 && pb->dtype != MDSD_BF16) return MDSD_E_DTYPE;
+    if (pb->kind != MDSD_PROBS && pb->kind != MDSD_LOGITS) return MDSD_E_DTYPE;
+    if (pb->B < 1 || pb->N < 1 || pb->V < 2 || pb->depth < 1) return MDSD_E_SHAPE;
+    if (pb->ld_d < pb->V || (need_target && pb->ld_t < pb->V)) return MDSD_E_SHAPE;
+    if (pb->k < 1 || pb->k > MDSD_MAX_K) return MDSD_E_K;
+    if (method == kSpecHub && pb->k != 2) return MDSD_E_K;
+    if (pb->kind == MDSD_LOGITS) {
+        if (!(pb->temp_draft > 0.f)) return MDSD_E_TEMP;
+        if (need_target && !(pb->temp_target > 0.f)) return MDSD_E_TEMP;
+    }
+    const int es = pb->dtype == MDSD_FP32 ? 4 : 2;
+    const int per_chunk = 16 / es;
+    // vocabulary bound of the per-slab partial sums kept in LDS
+    if ((int64_t)pb->V + per_chunk > (int64_t)kMaxSlabs * 64 * per_chunk) return MDSD_E_SHAPE;
+    if ((int64_t)pb->B * pb->N > INT_MAX) return MDSD_E_SHAPE;
+    const uintptr_t at = (uintptr_t)pb->target, ad = (uintptr_t)pb->draft;
+    if ((ad % es) != 0 || (need_target && (at % es) != 0)) return MDSD_E_ALIGN;
+    if (need_target) {
+        // every pair of rows must share its offset modulo 16 bytes
+        if ((at & 15) != (ad & 15)) return MDSD_E_ALIGN;
+        if (pb->B * (int64_t)pb->N > 1 && ((pb->ld_t * es) & 15) != ((pb->ld_d * es) & 15)) return MDSD_E_ALIGN;
+    }
+    int64_t n_internal = 0;
+    if (!pb->first_child) {
+        const int n = complete_tree_nodes(pb->k, pb->depth, &n_internal);
+        if (n != pb->N) return MDSD_E_SHAPE;
+    }
+    P->target = pb->target;
+    P->draft = pb->draft;
+    P->ld_t = pb->ld_t;
+    P->ld_d = pb->ld_d;
+    P->temp_target = pb->temp_target;
+    P->temp_draft = pb->temp_draft;
+    P->B = pb->B;
+    P->N = pb->N;
+    P->V = pb->V;
+    P->k = pb->k;
+    P->depth = pb->depth;
+    P->n_internal = (int)n_internal;
+    P->first_child = pb->first_child;
+    return MDSD_OK;
+}
+
+template <int METHOD>
+static void launch_verify(const mdsd_problem* pb, const Params& P, hipStream_t st)
+{
+    const dim3 grid((unsigned)(P.B * P.N)), block(kWG);
+    const bool lg = pb->kind == MDSD_LOGITS;
+    if (pb->dtype == MDSD_FP32) {
+        if (lg)
+            hipLaunchKernelGGL((verify_kernel<0, true, METHOD>), grid, block, 0, st, P);
+        else
+            hipLaunchKernelGGL((verify_kernel<0, false, METHOD>), grid, block, 0, st, P);
+    } else {
+        if (lg)
+            hipLaunchKernelGGL((verify_kernel<1, true, METHOD>), grid, block, 0, st, P);
+        else
+            hipLaunchKernelGGL((verify_kernel<1, false, METHOD>), grid, block, 0, st, P);
+    }
+}
+
+template <int METHOD>
+static void launch_draft(const mdsd_problem* pb, const Params& P, hipStream_t st)
+{
+    const dim3 grid((unsigned)(P.B * P.N)), block(kWG);
+    const bool lg = pb->kind == MDSD_LOGITS;
+    if (pb->dtype == MDSD_FP32) {
+        if (lg)
+            hipLaunchKernelGGL((draft_kernel<0, true, METHOD>), grid, block, 0, st, P);
+        else
+            hipLaunchKernelGGL((draft_kernel<0, false, METHOD>), grid, block, 0, st, P);
+    } else {
+        if (lg)
+            hipLaunchKernelGGL((draft_kernel<1, true, METHOD>), grid, block, 0, st, P);
+        else
+            hipLaunchKernelGGL((draft_kernel<1, false, METHOD>), grid, block, 0, st, P);
+    }
+}
+
+static int walk(const mdsd_problem* pb, const int32_t* outcome, const int32_t* token,
+                int32_t* accept_depth, int32_t* emitted, hipStream_t st)
+{
+    const int threads = 64;
+    hipLaunchKernelGGL(tree_walk_kernel, dim3((pb->B + threads - 1) / threads), dim3(threads), 0, st,
+                       outcome, token, pb->B, pb->N, pb->k, pb->depth, pb->first_child, accept_depth,
+                       emitted);
+    return hipGetLastError() == hipSuccess ? MDSD_OK : MDSD_E_LAUNCH;
+}
+
+static int verify_entry(int method, const mdsd_problem* pb, const int32_t* tokens, const float* u,
+                        const mdsd_result* out, void* stream)
+{
+    Params P = {};
+    const int rc = validate(pb, method, true, &P);
+    if (rc != MDSD_OK) return rc;
+    if (!tokens || !u || !out || !out->outcome || !out->token) return MDSD_E_NULL;
+    if ((out->accept_depth == nullptr) != (out->emitted == nullptr)) return MDSD_E_NULL;
+    P.tokens = tokens;
+    P.u = u;
+    P.outcome = out->outcome;
+    P.token = out->token;
+    P.resid_mass = out->resid_mass;
+    P.flags = out->flags;
+    P.resid_prob = out->resid_prob;
+    hipStream_t st = (hipStream_t)stream;
+    (void)hipGetLastError();
+    if (method == kSpecHub)
+        launch_verify<kSpecHub>(pb, P, st);
+    else if (method == kRRS)
+        launch_verify<kRRS>(pb, P, st);
+    else
+        launch_verify<kRRSw>(pb, P, st);
+    if (hipGetLastError() != hipSuccess) return MDSD_E_LAUNCH;
+    if (out->accept_depth) return walk(pb, out->outcome, out->token, out->accept_depth, out->emitted, st);
+    return MDSD_OK;
+}
+
+static int draft_entry(int method, const mdsd_problem* pb, const float* u, int32_t* tokens,
+                       int32_t* hub, int32_t* flags, void* stream)
+{
+    Params P = {};
+    const int rc = validate(pb, method, false, &P);
+    if (rc != MDSD_OK) return rc;
+    if (!u || !tokens) return MDSD_E_NULL;
+    P.u = u;
+    P.tokens_out = tokens;
+    P.hub_out = hub;
+    P.flags = flags;
+    hipStream_t st = (hipStream_t)stream;
+    (void)hipGetLastError();
+    if (method == kSpecHub)
+        launch_draft<kSpecHub>(pb, P, st);
+    else if (method == kRRS)
+        launch_draft<kRRS>(pb, P, st);
+    else
+        launch_draft<kRRSw>(pb, P, st);
+    return hipGetLastError() == hipSuccess ? MDSD_OK : MDSD_E_LAUNCH;
+}
+
+}  // namespace mdsd
+
+// ---------------------------------------------------------------- C ABI
+extern "C" {
+
+size_t mdsd_workspace_bytes(const mdsd_problem* pb)
+{
+    (void)pb;
+    return 0;  // every intermediate lives in registers and LDS
+}
+
+int spechub_draft(const mdsd_problem* pb, const float* u, int32_t* tokens, int32_t* hub, int32_t* flags,
+                  void* ws, size_t ws_bytes, void* stream)
+{
+    (void)ws;
+    (void)ws_bytes;
+    return mdsd::draft_entry(mdsd::kSpecHub, pb, u, tokens, hub, flags, stream);
+}
+
+int rrs_draft(const mdsd_problem* pb, const float* u, int32_t* tokens, int32_t* flags, void* ws,
+              size_t ws_bytes, void* stream)
+{
+    (void)ws;
+    (void)ws_bytes;
+    return mdsd::draft_entry(mdsd::kRRS, pb, u, tokens, nullptr, flags, stream);
+}
+
+int rrsw_draft(const mdsd_problem* pb, const float* u, int32_t* tokens, int32_t* flags, void* ws,
+               size_t ws_bytes, void* stream)
+{
+    (void)ws;
+    (void)ws_bytes;
+    return mdsd::draft_entry(mdsd::kRRSw, pb, u, tokens, nullptr, flags, stream);
+}
+
+int spechub_verify(const mdsd_problem* pb, const int32_t* tokens, const float* u, const mdsd_result* out,
+                   void* ws, size_t ws_bytes, void* stream)
+{
+    (void)ws;
+    (void)ws_bytes;
+    return mdsd::verify_entry(mdsd::kSpecHub, pb, tokens, u, out, stream);
+}
+
+int rrs_verify(const mdsd_problem* pb, const int32_t* tokens, const float* u, const mdsd_result* out,
+               void* ws, size_t ws_bytes, void* stream)
+{
+    (void)ws;
+    (void)ws_bytes;
+    return mdsd::verify_entry(mdsd::kRRS, pb, tokens, u, out, stream);
+}
+
+int rrsw_verify(const mdsd_problem* pb, const int32_t* tokens, const float* u, const mdsd_result* out,
+                void* ws, size_t ws_bytes, void* stream)
+{
+    (void)ws;
+    (void)ws_bytes;
+    return mdsd::verify_entry(mdsd::kRRSw, pb, tokens, u, out, stream);
+}
+
+int mdsd_tree_walk(const mdsd_problem* pb, const int32_t* outcome, const int32_t* token,
+                   int32_t* accept_depth, int32_t* emitted, void* stream)
+{
+    if (!pb || !outcome || !token || !accept_depth || !emitted) return MDSD_E_NULL;
+    if (pb->B < 1 || pb->N < 1 || pb->depth < 1) return MDSD_E_SHAPE;
+    if (pb->k < 1 || pb->k > MDSD_MAX_K) return MDSD_E_K;
+    (void)hipGetLastError();
+    return mdsd::walk(pb, outcome, token, accept_depth, emitted, (hipStream_t)stream);
+}
+
+int mdsd_philox_uniform(uint64_t seed, uint32_t stream_id, int64_t rows, int32_t slots, float* out,
+                        uint32_t* words, void* stream)
+{
+    if (!out && !words) return MDSD_E_NULL;
+    if (rows < 0 || slots < 1) return MDSD_E_SHAPE;
+    if (rows == 0) return MDSD_OK;
+    const int64_t n = rows * ((slots + 3) >> 2);
+    const int threads = 256;
+    const int64_t blocks = (n + threads - 1) / threads;
+    if (blocks > INT_MAX) return MDSD_E_SHAPE;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(mdsd::philox_uniform_kernel, dim3((unsigned)blocks), dim3(threads), 0,
+                       (hipStream_t)stream, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, rows,
+                       (int)slots, out, words);
+    return hipGetLastError() == hipSuccess ? MDSD_OK : MDSD_E_LAUNCH;
+}
+
+const char* mdsd_strerror(int code)
+{
+    switch (code) {
+    case MDSD_OK: return "ok";
+    case MDSD_E_NULL: return "a required pointer is NULL";
+    case MDSD_E_SHAPE: return "bad shape: B, N, V, ld, depth or tree/N mismatch";
+    case MDSD_E_K: return "k out of range (SpecHub needs k == 2)";
+    case MDSD_E_TEMP: return "temperature must be > 0";
+    case MDSD_E_DTYPE: return "unknown dtype or kind";
+    case MDSD_E_ALIGN: return "pointer not element-aligned, or target/draft rows differ modulo 16 bytes";
+    case MDSD_E_WORKSPACE: return "workspace too small";
+    case MDSD_E_LAUNCH: return "HIP launch failed";
+    default: return "unknown status";
+    }
+}
+
+int mdsd_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,163 @@
+// Building blocks shared by the draft and verify kernels: the slab loop over
+// one or two rows, per-slab partial sums kept in LDS, and the two-level
+// inverse-CDF search that uses them.
+//
+// Layout of the work inside a workgroup of kWaves wavefronts: slab s (64
+// chunks of 16 bytes) belongs to wave s % kWaves.  A pass that needs an
+// index-ordered prefix later (an inverse-CDF draw) leaves one partial sum per
+// slab in LDS; the search then scans those sums, picks the slab, and only
+// that slab is recomputed element by element.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "row_io.h"
+#include "wave_ops.h"
+
+namespace mdsd {
+
+constexpr int kWG = 256;
+constexpr int kWaves = kWG / kWave;
+constexpr int kMaxSlabs = 2048;
+constexpr float kLog2e = 1.44269504088896340736f;
+
+// stored element -> unnormalised probability.  Logits: 2^(l*s - ms) with
+// s = log2(e)/T and ms = max*s; probabilities pass through.
+template <bool LOGITS>
+struct ToWeight {
+    float s, ms;
+    __device__ __forceinline__ float operator()(float l) const
+    {
+        if constexpr (LOGITS)
+            return __builtin_amdgcn_exp2f(fmaf(l, s, -ms));
+        else
+            return l;
+    }
+    static __device__ __forceinline__ float fill()
+    {
+        return LOGITS ? -__builtin_inff() : 0.f;
+    }
+};
+
+// fixed-shape sum of one lane's chunk; every slab sum is built from it, so a
+// recomputed slab reproduces the stored sum bit for bit
+template <int E>
+__device__ __forceinline__ float chunk_sum(const float (&w)[E])
+{
+    if constexpr (E == 8)
+        return ((w[0] + w[1]) + (w[2] + w[3])) + ((w[4] + w[5]) + (w[6] + w[7]));
+    else
+        return (w[0] + w[1]) + (w[2] + w[3]);
+}
+
+// body(slab, chunk, a[E])           for one row
+template <int DT, class Body>
+__device__ __forceinline__ void slab_loop1(const RowView& ra, float fill, Body body)
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int s = wave; s < ra.nslab; s += kWaves) {
+        float a[E];
+        load_chunk<DT>(ra, s * 64 + lane, fill, a);
+        body(s, s * 64 + lane, a);
+    }
+}
+
+// body(slab, chunk, a[E], b[E])     for two rows with the same head
+template <int DT, class Body>
+__device__ __forceinline__ void slab_loop2(const RowView& ra, const RowView& rb, float fill,
+                                           Body body)
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int s = wave; s < ra.nslab; s += kWaves) {
+        float a[E], b[E];
+        load_chunk<DT>(ra, s * 64 + lane, fill, a);
+        load_chunk<DT>(rb, s * 64 + lane, fill, b);
+        body(s, s * 64 + lane, a, b);
+    }
+}
+
+// store one slab's sum: every lane passes its chunk sum, lane 63 writes
+__device__ __forceinline__ void store_slab_sum(float* slab_w, int s, float lane_sum)
+{
+    const float t = wave_scan_add(lane_sum);
+    if ((threadIdx.x & 63) == 63) slab_w[s] = t;
+}
+
+// Sum of the slab sums, in slab order.  Every wave computes it on its own
+// (identical arithmetic, so identical bits) -- no broadcast needed.
+template <class SlabVal>
+__device__ __forceinline__ float slab_total(int nslab, SlabVal slab_val)
+{
+    const int lane = threadIdx.x & 63;
+    float W = 0.f;
+    for (int base = 0; base < nslab; base += 64) {
+        const float v = (base + lane < nslab) ? slab_val(base + lane) : 0.f;
+        W += wave_sum(v);
+    }
+    return W;
+}
+
+// Inverse CDF: virtual index of the first element whose running sum exceeds
+// u * W, where W = slab_total.  slab_val(i) gives the sum of slab i;
+// weights(s, w) recomputes this lane's chunk of slab s.  Returns -1 when
+// W == 0.  If rounding leaves no crossing, the last element with positive
+// weight is returned.  Every wave runs the search redundantly.
+template <int E, class SlabVal, class Weights>
+__device__ __forceinline__ int icdf_slabs(int nslab, float u, float W, SlabVal slab_val,
+                                          Weights weights)
+{
+    const int lane = threadIdx.x & 63;
+    if (!(W > 0.f)) return -1;
+    float t = u * W;
+    float carry = 0.f, excl_hit = 0.f;
+    int s_hit = -1, last_pos = -1;
+    for (int base = 0; base < nslab; base += 64) {
+        const float v = (base + lane < nslab) ? slab_val(base + lane) : 0.f;
+        const float incl = wave_scan_add(v);
+        const float excl = carry + wave_shift_up(incl, 0.f);
+        const unsigned long long hit = __ballot(carry + incl > t);
+        const unsigned long long pos = __ballot(v > 0.f);
+        if (hit) {
+            const int l = __ffsll(hit) - 1;
+            s_hit = base + l;
+            excl_hit = __shfl(excl, l, 64);
+            break;
+        }
+        if (pos) last_pos = base + 63 - __clzll(pos);
+        carry += lane_bcast(incl, 63);
+    }
+    if (s_hit < 0) {  // t >= W after rounding: take the last positive element
+        if (last_pos < 0) return -1;
+        s_hit = last_pos;
+        t = __builtin_inff();
+    }
+    float w[E];
+    weights(s_hit, w);
+    const float ls = chunk_sum<E>(w);
+    const float incl = wave_scan_add(ls);
+    const float lane_excl = wave_shift_up(incl, 0.f);
+    const unsigned long long hit = __ballot(excl_hit + incl > t);
+    const unsigned long long pos = __ballot(ls > 0.f);
+    int l;
+    if (hit) {
+        l = __ffsll(hit) - 1;
+    } else {
+        if (!pos) return -1;
+        l = 63 - __clzll(pos);
+        t = __builtin_inff();
+    }
+    float run = excl_hit + lane_excl;
+    int e_sel = -1, e_last = -1;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        if (w[e] > 0.f) e_last = e;
+        run += w[e];
+        if (e_sel < 0 && run > t) e_sel = e;
+    }
+    if (e_sel < 0) e_sel = e_last;
+    const int vidx = (e_sel < 0) ? -1 : (s_hit * 64 + lane) * E + e_sel;
+    return __shfl(vidx, l, 64);
+}
+
+}  // namespace mdsd

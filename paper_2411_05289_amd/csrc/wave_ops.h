@@ -1,0 +1,129 @@
+// Wavefront (64 lanes) and workgroup reductions for gfx950, built on DPP
+// row shifts and row broadcasts so that no LDS traffic is needed inside a
+// wave.  Every reduction has a fixed association order: results are
+// bit-reproducible from launch to launch.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace mdsd {
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float as_f(int v) { return __builtin_bit_cast(float, v); }
+__device__ __forceinline__ int as_i(float v) { return __builtin_bit_cast(int, v); }
+
+// v_mov_b32 with a DPP control; lanes without a source (or masked rows) read `old`.
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ float dpp(float old, float v)
+{
+    return as_f(__builtin_amdgcn_update_dpp(as_i(old), as_i(v), CTRL, ROW_MASK, 0xf, false));
+}
+
+constexpr int kRowShr1 = 0x111, kRowShr2 = 0x112, kRowShr4 = 0x114, kRowShr8 = 0x118;
+constexpr int kRowBcast15 = 0x142, kRowBcast31 = 0x143, kWaveShr1 = 0x138;
+
+// Inclusive prefix sum over the 64 lanes; lane 63 ends with the wave total.
+__device__ __forceinline__ float wave_scan_add(float v)
+{
+    v += dpp<kRowShr1>(0.f, v);
+    v += dpp<kRowShr2>(0.f, v);
+    v += dpp<kRowShr4>(0.f, v);
+    v += dpp<kRowShr8>(0.f, v);
+    v += dpp<kRowBcast15, 0xa>(0.f, v);
+    v += dpp<kRowBcast31, 0xc>(0.f, v);
+    return v;
+}
+
+__device__ __forceinline__ float wave_scan_max(float v)
+{
+    const float ninf = -__builtin_inff();
+    v = fmaxf(v, dpp<kRowShr1>(ninf, v));
+    v = fmaxf(v, dpp<kRowShr2>(ninf, v));
+    v = fmaxf(v, dpp<kRowShr4>(ninf, v));
+    v = fmaxf(v, dpp<kRowShr8>(ninf, v));
+    v = fmaxf(v, dpp<kRowBcast15, 0xa>(ninf, v));
+    v = fmaxf(v, dpp<kRowBcast31, 0xc>(ninf, v));
+    return v;
+}
+
+__device__ __forceinline__ float lane_bcast(float v, int lane)
+{
+    return as_f(__builtin_amdgcn_readlane(as_i(v), lane));
+}
+
+__device__ __forceinline__ float wave_sum(float v) { return lane_bcast(wave_scan_add(v), 63); }
+__device__ __forceinline__ float wave_max(float v) { return lane_bcast(wave_scan_max(v), 63); }
+
+// value of the lane below (lane 0 reads `fill`)
+__device__ __forceinline__ float wave_shift_up(float v, float fill)
+{
+    return dpp<kWaveShr1>(fill, v);
+}
+
+// Workgroup reductions through a small double-buffered LDS area: one barrier
+// per call; two consecutive calls never touch the same buffer.
+template <int WAVES>
+struct BlockScratch {
+    float buf[2][WAVES][4];
+    int ibuf[2][WAVES];
+};
+
+template <int WAVES, int NV>
+__device__ __forceinline__ void block_sum(float (&v)[NV], BlockScratch<WAVES>& s, int& phase)
+{
+    static_assert(NV <= 4, "at most four values per reduction");
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        float t = wave_scan_add(v[i]);
+        if (lane == 63) s.buf[phase][wave][i] = t;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        float t = 0.f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) t += s.buf[phase][w][i];
+        v[i] = t;
+    }
+    phase ^= 1;
+}
+
+template <int WAVES, int NV>
+__device__ __forceinline__ void block_max(float (&v)[NV], BlockScratch<WAVES>& s, int& phase)
+{
+    static_assert(NV <= 4, "at most four values per reduction");
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        float t = wave_scan_max(v[i]);
+        if (lane == 63) s.buf[phase][wave][i] = t;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        float t = s.buf[phase][0][i];
+#pragma unroll
+        for (int w = 1; w < WAVES; ++w) t = fmaxf(t, s.buf[phase][w][i]);
+        v[i] = t;
+    }
+    phase ^= 1;
+}
+
+// Smallest index over the workgroup (INT_MAX where a thread has none).
+template <int WAVES>
+__device__ __forceinline__ int block_min_index(int idx, BlockScratch<WAVES>& s, int& phase)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) idx = min(idx, __shfl_xor(idx, off, 64));
+    if (lane == 0) s.ibuf[phase][wave] = idx;
+    __syncthreads();
+    int r = s.ibuf[phase][0];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) r = min(r, s.ibuf[phase][w]);
+    phase ^= 1;
+    return r;
+}
+
+}  // namespace mdsd

@@ -1,0 +1,235 @@
+"""Shared machinery of the GPU parity tests: run the HIP library and the CPU
+oracle on the same rows, tokens and uniforms and compare element by element.
+
+Bar (stated by the benchmark spec): accepted slots, tokens and accept
+depths bit-exact, except at nodes where the oracle reports that a uniform lay
+within 1e-6 of a decision threshold (those nodes are counted and reported, and
+must stay rare); residual mass within 1e-5 relative; residual probabilities
+within 1e-5 of the larger of the two terms they are the difference of.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+from paper_2411_05289_amd import binding as B
+from paper_2411_05289_amd.workloads import Workload, rows_as_numpy
+
+BAND = 1e-6
+RESID_MASS_ATOL = 5e-7
+METHODS = {"spechub": oracle.SPECHUB, "rrs": oracle.RRS, "rrsw": oracle.RRSW}
+DRAFT = {"spechub": B.spechub_draft, "rrs": B.rrs_draft, "rrsw": B.rrsw_draft}
+VERIFY = {"spechub": B.spechub_verify, "rrs": B.rrs_verify, "rrsw": B.rrsw_verify}
+
+
+def _np(t):
+    return t.detach().cpu().numpy()
+
+
+def oracle_kwargs(wl: Workload):
+    return dict(dtype=oracle.FP32 if wl.dtype == "fp32" else oracle.BF16,
+                kind=oracle.LOGITS if wl.kind == "logits" else oracle.PROBS,
+                k=wl.k, depth=wl.depth,
+                first_child=None if wl.first_child is None else _np(wl.first_child))
+
+
+def uniforms(wl: Workload, seed: int):
+    """Draft and verify uniforms made on the GPU by the library's Philox."""
+    rows = wl.B * wl.N
+    u_d = B.philox_uniform(seed, 1, rows, wl.k, device=wl.draft.device).view(wl.B, wl.N, wl.k)
+    u_v = B.philox_uniform(seed, 2, rows, wl.k + 1, device=wl.draft.device).view(wl.B, wl.N, wl.k + 1)
+    return u_d, u_v
+
+
+def check_case(method: str, wl: Workload, seed: int = 0, seqs=None, full_outputs: bool = True,
+               nthreads: int = 8, report=None):
+    """Run draft + verify of `method` on the whole workload on the GPU; compare the
+    sequences `seqs` (default: all) with the oracle.  Returns a dict of counts."""
+    assert wl.draft.is_cuda
+    pb = B.Problem.from_workload(wl)
+    u_d, u_v = uniforms(wl, seed)
+    seqs = list(range(wl.B)) if seqs is None else list(seqs)
+    idx = torch.as_tensor(seqs, device=wl.draft.device)
+    ok = oracle_kwargs(wl)
+
+    t_np = rows_as_numpy(wl.target[idx])
+    d_np = rows_as_numpy(wl.draft[idx])
+    ud_np, uv_np = _np(u_d[idx]), _np(u_v[idx])
+
+    # ---- draft
+    g_d = DRAFT[method](pb, u_d)
+    o_d = oracle.batch_draft(METHODS[method], d_np, ud_np, temp_draft=wl.temp_draft,
+                             nthreads=nthreads, **ok)
+    g_tok = _np(g_d["tokens"][idx])
+    near_d = o_d["margin"] < BAND
+    # children of a near-threshold node may differ; everything else must not
+    internal = _internal_mask(wl)
+    child_ok = np.ones_like(g_tok, dtype=bool)
+    for n in np.nonzero(internal)[0]:
+        c0 = _first_child(wl, n)
+        bad = near_d[:, n]
+        child_ok[bad, c0:c0 + wl.k] = False
+    mism_d = (g_tok != o_d["tokens"]) & child_ok
+    assert not mism_d.any(), "draft tokens differ at %s" % (np.argwhere(mism_d)[:5],)
+    assert (g_tok[:, 0] == -1).all()
+    if method == "spechub":
+        g_hub = _np(g_d["hub"][idx])
+        assert (g_hub == o_d["hub"]).all(), "hub differs"
+    assert (_np(g_d["flags"][idx])[:, internal] == o_d["flags"][:, internal]).all()
+
+    # ---- verify, on the oracle's tokens so that the two stages are judged separately
+    tokens = g_d["tokens"].clone()
+    tokens[idx] = torch.from_numpy(o_d["tokens"]).to(tokens.device)
+    o_v = oracle.batch_verify(METHODS[method], t_np, d_np, o_d["tokens"], uv_np,
+                              temp_target=wl.temp_target, temp_draft=wl.temp_draft,
+                              want_resid_prob=full_outputs and wl.V <= 4096, nthreads=nthreads, **ok)
+    g_fast = VERIFY[method](pb, tokens, u_v, resid_mass=False, flags=True, walk=True)
+    near = o_v["margin"] < BAND
+    out = dict(nodes=near.size, near_threshold_draft=int(near_d[:, internal].sum()),
+               near_threshold_verify=int(near.sum()))
+    ctx = dict(method=method, wl=wl, t_np=t_np, d_np=d_np, tokens=o_d["tokens"], uv=uv_np)
+    out["mismatch_in_band"] = _compare_nodes(g_fast, o_v, idx, near, "early-exit", ctx)
+    _compare_walk(wl, g_fast, o_v, idx, near)
+
+    if full_outputs:
+        g_full = VERIFY[method](pb, tokens, u_v, resid_mass=True, flags=True, walk=True,
+                                resid_prob=wl.V <= 4096)
+        _compare_nodes(g_full, o_v, idx, near, "full", ctx)
+        rm_g, rm_o = _np(g_full["resid_mass"][idx]).astype(np.float64), o_v["resid_mass"]
+        valid = _np(g_full["outcome"][idx]) >= -1
+        rel = np.abs(rm_g - rm_o) / np.maximum(np.abs(rm_o), 1e-30)
+        # 1e-5 relative, plus the rounding of the O(1) operands the mass is a difference of
+        # (each term max(p - c q, 0) carries a few fp32 ulps of max(p, c q), and those sum to <= 2)
+        bad = valid & (np.abs(rm_g - rm_o) > 1e-5 * np.abs(rm_o) + RESID_MASS_ATOL)
+        assert not bad.any(), "resid_mass off: %s gpu %s oracle %s" % (
+            np.argwhere(bad)[:5], rm_g[bad][:5], rm_o[bad][:5])
+        out["resid_mass_max_rel"] = float(rel[valid & (rm_o > 1e-6)].max(initial=0.0))
+        if "resid_prob" in g_full:
+            rp_g = _np(g_full["resid_prob"][idx]).astype(np.float64)
+            rp_o = o_v["resid_prob"]
+            tol = _resid_prob_tolerance(method, wl, t_np, d_np, o_v, o_d["tokens"])
+            diff = np.abs(rp_g - rp_o)
+            ok_nodes = valid & (o_v["flags"] == 0) & (rm_o > 1e-6)
+            bad = (diff > tol) & ok_nodes[:, :, None]
+            assert not bad.any(), "resid_prob off at %s (diff %g)" % (np.argwhere(bad)[:5], diff[bad].max())
+            out["resid_prob_max_abs"] = float(diff[ok_nodes].max(initial=0.0))
+    if report is not None:
+        report.append((method, wl.name, out))
+    # An inverse-CDF draw lands within 1e-6 of a token boundary whenever it hits a token of
+    # probability < 2e-6, so on LLM-sized vocabularies a few percent of the draws are "near";
+    # the nodes where the two sides then really differ must stay a small fraction.
+    assert out["mismatch_in_band"] <= 2 + 0.02 * near.size, out
+    return out
+
+
+def _internal_mask(wl: Workload):
+    if wl.first_child is not None:
+        return _np(wl.first_child) >= 0
+    n = np.arange(wl.N)
+    return wl.k * n + wl.k < wl.N
+
+
+def _first_child(wl: Workload, n: int) -> int:
+    if wl.first_child is not None:
+        return int(_np(wl.first_child)[n])
+    return wl.k * n + 1
+
+
+def _to_f64(rows, dtype):
+    if dtype == "fp32":
+        return rows.astype(np.float64)
+    return (rows.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def _node_draw_weights(ctx, b, n):
+    """Weights and uniform of the inverse-CDF draw the oracle made at node (b, n)."""
+    wl, method = ctx["wl"], ctx["method"]
+
+    def prob(rows, T):
+        x = _to_f64(rows, wl.dtype)
+        return oracle.softmax(x, float(np.float32(T))) if wl.kind == "logits" else x
+
+    p = prob(ctx["t_np"][b, n], wl.temp_target)
+    u = float(ctx["uv"][b, n, wl.k])
+    if not _internal_mask(wl)[n]:
+        return p, u
+    q = prob(ctx["d_np"][b, n], wl.temp_draft)
+    c0 = _first_child(wl, n)
+    xs = [int(t) for t in ctx["tokens"][b, c0:c0 + wl.k]]
+    r = [float(v) for v in ctx["uv"][b, n, :wl.k]]
+    if method == "spechub":
+        a = oracle.argmax(_to_f64(ctx["d_np"][b, n], wl.dtype))
+        return oracle.spechub_verify(p, q, a, xs[0], xs[1], r[0], r[1], u, want_w=True)["w"], u
+    return oracle.rrs_verify(p, q, xs, r, u, method == "rrsw", want_P=True)["P"], u
+
+
+def _compare_nodes(g, o, idx, near, label, ctx=None):
+    """Outcomes and tokens equal outside the near-threshold band.  Inside it a differing
+    token must still be a valid draw: its own interval of the oracle's cumulative sums lies
+    within the band of the threshold u * W.  Returns the number of differing nodes."""
+    oc_g, tk_g = _np(g["outcome"][idx]), _np(g["token"][idx])
+    differ = (oc_g != o["outcome"]) | (tk_g != o["token"])
+    mism = differ & ~near
+    assert not mism.any(), "%s: outcome/token differ at %s" % (label, np.argwhere(mism)[:5])
+    fl = _np(g["flags"][idx])
+    assert ((fl == o["flags"]) | near).all(), "%s: flags differ" % label
+    if ctx is not None:
+        for b, n in np.argwhere(differ & near)[:200]:
+            if oc_g[b, n] != -1 or o["outcome"][b, n] != -1:
+                continue  # an accept test within the band: either decision is admissible
+            w, u = _node_draw_weights(ctx, b, n)
+            c = np.cumsum(w)
+            W, t, x = c[-1], u * c[-1], tk_g[b, n]
+            assert 0 <= x < w.size and w[x] > 0, "%s: drew a massless token at %s" % (label, (b, n))
+            dist = max(c[x] - w[x] - t, t - c[x], 0.0)
+            assert dist <= 2 * BAND * W, "%s: token at %s is %g W away from the draw" % (label, (b, n), dist / W)
+    return int(differ.sum())
+
+
+def _compare_walk(wl, g, o, idx, near):
+    oc_g, tk_g = _np(g["outcome"][idx]), _np(g["token"][idx])
+    ad_g, em_g = _np(g["accept_depth"][idx]), _np(g["emitted"][idx])
+    fc = None if wl.first_child is None else _np(wl.first_child)
+    for i in range(oc_g.shape[0]):
+        # the walk is integer work: exact on the GPU's own node results ...
+        d, em = oracle.tree_walk(oc_g[i], tk_g[i], wl.k, wl.depth, fc)
+        assert d == ad_g[i] and (em == em_g[i]).all()
+        # ... and equal to the oracle's walk whenever no node of the tree was near a threshold
+        if not near[i].any():
+            assert ad_g[i] == o["accept_depth"][i] and (em_g[i] == o["emitted"][i]).all()
+
+
+def _resid_prob_tolerance(method, wl, t_np, d_np, o_v, tokens_np):
+    """1e-5 of the larger operand of the subtraction each residual entry comes from,
+    in units of the normalised residual."""
+    Bn, N, V = t_np.shape
+    tol = np.empty((Bn, N, V))
+    dt = oracle.FP32 if wl.dtype == "fp32" else oracle.BF16
+
+    def to_prob(rows, T):
+        x = rows.astype(np.float64) if dt == oracle.FP32 else \
+            (rows.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        return oracle.softmax(x, float(np.float32(T))) if wl.kind == "logits" else x
+
+    for b in range(Bn):
+        for n in range(N):
+            p = to_prob(t_np[b, n], wl.temp_target)
+            q = to_prob(d_np[b, n], wl.temp_draft)
+            if method == "spechub":
+                a = int(np.argmax(q))
+                scale = np.maximum(p, q / max(1.0 - q[a], 1e-30))
+            else:
+                # residual = max(p - c q, 0) with c <= k * (largest rescaling of q)
+                cmax = float(wl.k)
+                c0 = _first_child(wl, n) if _internal_mask(wl)[n] else -1
+                if method == "rrsw" and c0 >= 0:
+                    xs = np.unique(tokens_np[b, c0:c0 + wl.k])
+                    cmax /= max(1.0 - q[xs[xs >= 0]].sum(), 1e-30)
+                scale = np.maximum(p, cmax * q)
+            tol[b, n] = 1e-5 * scale / max(o_v["resid_mass"][b, n], 1e-30) + 1e-9
+    return tol
+
+
+def tokens_per_step(accept_depth) -> float:
+    return float(np.mean(np.asarray(accept_depth, dtype=np.float64) + 1.0))

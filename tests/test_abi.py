@@ -1,0 +1,96 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the
+header declares, and rejects what the host can detect before anything is
+launched (no GPU is touched: every call below fails validation)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2411_05289_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "mdsd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\(", text)) - {"defined"})
+
+
+def test_header_symbols_are_exported():
+    L = B.lib()
+    names = declared_functions()
+    assert set(B.EXPORTS) <= set(names)
+    for n in names:
+        assert hasattr(L, n), "libmdsd.so does not export %s" % n
+
+
+def test_version_and_strerror():
+    assert B.version() >= 100
+    assert B.strerror(0) == "ok"
+    assert "NULL" in B.strerror(-1)
+
+
+def _problem(**kw):
+    p = B._Problem()
+    p.target, p.draft = 0x1000, 0x2000     # never dereferenced: validation fails first
+    p.ld_t = p.ld_d = 64
+    p.dtype, p.kind = B.BF16, B.LOGITS
+    p.temp_target = p.temp_draft = 1.0
+    p.B, p.N, p.V, p.k, p.depth = 1, 3, 64, 2, 2
+    p.first_child = None
+    for k, v in kw.items():
+        setattr(p, k, v)
+    return p
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(V=1), -2), (dict(B=0), -2), (dict(N=4), -2), (dict(ld_t=8), -2), (dict(depth=0), -2),
+    (dict(k=3, N=4), -3), (dict(k=0), -3), (dict(temp_target=0.0), -4), (dict(temp_draft=-1.0), -4),
+    (dict(dtype=7), -5), (dict(kind=2), -5), (dict(target=0x1002, draft=0x2000), -6),
+    (dict(target=0x1001), -6), (dict(draft=None), -1), (dict(ld_t=65), -6),
+])
+def test_spechub_verify_rejects_bad_problems(kw, code):
+    L = B.lib()
+    p = _problem(**kw)
+    res = B._Result()
+    res.outcome, res.token = 0x3000, 0x4000
+    rc = L.spechub_verify(C.byref(p), C.c_void_p(0x5000), C.c_void_p(0x6000), C.byref(res), None, 0, None)
+    assert rc == code
+
+
+def test_null_arguments():
+    L = B.lib()
+    p = _problem()
+    res = B._Result()
+    assert L.spechub_verify(C.byref(p), None, C.c_void_p(0x6000), C.byref(res), None, 0, None) == -1
+    res.outcome, res.token = 0x3000, 0x4000
+    res.accept_depth = 0x7000          # emitted missing
+    assert L.rrs_verify(C.byref(p), C.c_void_p(0x5000), C.c_void_p(0x6000), C.byref(res), None, 0, None) == -1
+    assert L.spechub_draft(C.byref(p), None, C.c_void_p(0x5000), None, None, None, 0, None) == -1
+    assert L.rrs_draft(None, C.c_void_p(0x5000), C.c_void_p(0x5000), None, None, 0, None) == -1
+    assert L.mdsd_philox_uniform(1, 0, 4, 4, None, None, None) == -1
+    assert L.mdsd_philox_uniform(1, 0, 4, 0, C.c_void_p(0x5000), None, None) == -2
+
+
+def test_rrs_accepts_k_up_to_8_and_rejects_9():
+    L = B.lib()
+    res = B._Result()
+    p = _problem(k=9, N=10, depth=2)
+    assert L.rrs_verify(C.byref(p), C.c_void_p(0x5000), C.c_void_p(0x6000), C.byref(res), None, 0, None) == -3
+    p = _problem(k=2, N=3, V=10**7, ld_t=10**7, ld_d=10**7)
+    assert L.rrsw_verify(C.byref(p), C.c_void_p(0x5000), C.c_void_p(0x6000), C.byref(res), None, 0, None) == -2
+
+
+def test_workspace_is_zero():
+    p = _problem()
+    assert B.lib().mdsd_workspace_bytes(C.byref(p)) == 0
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    t = torch.zeros((1, 3, 64), dtype=torch.bfloat16)
+    pb = B.Problem(t, t, B.LOGITS, 2, 2)
+    with pytest.raises(ValueError):
+        B.spechub_verify(pb, torch.zeros((1, 3), dtype=torch.int32), torch.zeros((1, 3, 3)))

@@ -1,0 +1,245 @@
+"""GPU parity: the HIP library against the fp64 oracle, through the C ABI, on
+the same seeded rows, tokens and Philox uniforms (see tests/parity.py for the
+bar).  Sizes span several slabs and ragged tails; the large configurations run
+at full size on the GPU and are compared on sampled sequences."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2411_05289_amd import binding as B
+from paper_2411_05289_amd import workloads as W
+from parity import METHODS, check_case, tokens_per_step, _np
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+ALL = ["spechub", "rrs", "rrsw"]
+
+
+def note(request, out):
+    print("\n[parity] %s: %s" % (request.node.name, out), flush=True)
+
+
+# ----------------------------------------------------------------- Philox
+def test_philox_words_match_oracle():
+    for seed, stream, rows, slots in ((0, 1, 1000, 3), (2 ** 40 + 5, 7, 257, 9), (1, 0, 5, 1)):
+        u, w = B.philox_uniform(seed, stream, rows, slots, device=DEV, want_words=True)
+        uo, wo = oracle.philox_uniform(seed, stream, rows, slots, want_words=True)
+        assert (_np(w).view(np.uint32) == wo).all()
+        assert (_np(u) == uo).all()
+
+
+# ----------------------------------------------------------------- the five configurations
+@pytest.mark.parametrize("method", ALL)
+def test_config1_tiny_probs(method, request):
+    wl = W.config(1, device=DEV)
+    note(request, check_case(method, wl, seed=0))
+
+
+@pytest.mark.parametrize("method", ALL)
+def test_config2_fp32_logits(method, request):
+    wl = W.config(2, device=DEV)
+    note(request, check_case(method, wl, seed=0))
+    # more trees of the same recipe, so that every branch of the method is visited
+    wl = W.config(2, device=DEV, B=24, seed=3)
+    note(request, check_case(method, wl, seed=3, full_outputs=False))
+
+
+@pytest.mark.parametrize("method", ALL)
+def test_config3_bf16_headline(method, request):
+    wl = W.config(3, device=DEV)
+    note(request, check_case(method, wl, seed=0))
+
+
+@pytest.mark.parametrize("method", ALL)
+def test_config4_large_vocab_sampled(method, request):
+    wl = W.config(4, device=DEV)
+    seqs = [0, 1, 37, 100, 255]
+    note(request, check_case(method, wl, seed=0, seqs=seqs))
+
+
+@pytest.mark.parametrize("method", ["rrs", "rrsw"])
+def test_config5_four_drafts_sampled(method, request):
+    wl = W.config(5, device=DEV)                     # k = 4, depth 3; every 4th sequence near-uniform
+    note(request, check_case(method, wl, seed=0, seqs=[0, 3, 7, 64, 127]))
+
+
+def test_config5_spechub_sampled(request):
+    wl = W.config(5, device=DEV, k=2, depth=4)
+    note(request, check_case("spechub", wl, seed=0, seqs=[0, 3, 7, 64, 127]))
+
+
+# ----------------------------------------------------------------- ragged and misaligned rows
+@pytest.mark.parametrize("method", ALL)
+@pytest.mark.parametrize("V,dtype", [(2, torch.float32), (7, torch.float32), (50, torch.float32),
+                                     (1003, torch.float32), (5, torch.bfloat16), (777, torch.bfloat16),
+                                     (4099, torch.bfloat16)])
+def test_ragged_vocabularies(method, V, dtype, request):
+    """ld = V: row starts fall on every 16-byte phase, tails are partial chunks."""
+    k, depth = 2, 3
+    if method == "rrsw" and V < 3:
+        pytest.skip("cannot draw two distinct tokens plus a residual from V = 2")
+    N = W.tree_nodes(k, depth)
+    t, d = W.llm_like_logits(16, N, V, logit_std=2.0, draft_noise_std=1.0, dtype=dtype, seed=V, device=DEV)
+    wl = W.Workload("ragged_V%d" % V, 16, N, V, k, depth, "fp32" if dtype == torch.float32 else "bf16",
+                    "logits", 0.9, 1.1, t, d)
+    note(request, check_case(method, wl, seed=V))
+
+
+@pytest.mark.parametrize("method", ALL)
+def test_padded_rows_and_offset_base(method, request):
+    """ld > V and a base pointer that is not 16-byte aligned."""
+    k, depth, V, ld, Bn = 2, 3, 300, 312, 8
+    N = W.tree_nodes(k, depth)
+    t, d = W.llm_like_logits(Bn, N, V, logit_std=3.0, draft_noise_std=1.5, dtype=torch.bfloat16, seed=9, device=DEV)
+    big_t = torch.full((Bn * N * ld + 3,), 77.0, dtype=torch.bfloat16, device=DEV)
+    big_d = torch.full((Bn * N * ld + 3,), -77.0, dtype=torch.bfloat16, device=DEV)
+    tv = big_t[3:].view(Bn, N, ld)[:, :, :V]
+    dv = big_d[3:].view(Bn, N, ld)[:, :, :V]
+    tv.copy_(t)
+    dv.copy_(d)
+    wl = W.Workload("padded", Bn, N, V, k, depth, "bf16", "logits", 1.0, 1.0, tv, dv)
+    # the oracle reads contiguous copies of the same values
+    pb = B.Problem.from_workload(wl)
+    u_v = B.philox_uniform(4, 2, Bn * N, k + 1, device=DEV).view(Bn, N, k + 1)
+    u_d = B.philox_uniform(4, 1, Bn * N, k, device=DEV).view(Bn, N, k)
+    from parity import DRAFT, VERIFY
+    g_d = DRAFT[method](pb, u_d)
+    wl_c = W.Workload("padded_c", Bn, N, V, k, depth, "bf16", "logits", 1.0, 1.0, t.contiguous(), d.contiguous())
+    pb_c = B.Problem.from_workload(wl_c)
+    g_dc = DRAFT[method](pb_c, u_d)
+    assert (g_d["tokens"] == g_dc["tokens"]).all()
+    a = VERIFY[method](pb, g_d["tokens"], u_v, resid_mass=True)
+    c = VERIFY[method](pb_c, g_d["tokens"], u_v, resid_mass=True)
+    for key in ("outcome", "token", "accept_depth", "emitted"):
+        assert (a[key] == c[key]).all(), key
+    # a different 16-byte phase regroups the partial sums: same value up to rounding
+    assert torch.allclose(a["resid_mass"], c["resid_mass"], rtol=1e-5, atol=5e-7)
+    note(request, check_case(method, wl_c, seed=4))
+
+
+# ----------------------------------------------------------------- temperatures
+@pytest.mark.parametrize("method", ALL)
+@pytest.mark.parametrize("T", [0.3, 0.7, 2.0])
+def test_temperatures(method, T, request):
+    wl = W.config(2, device=DEV, B=8, V=4000, seed=11)
+    wl.temp_target = T
+    wl.temp_draft = T
+    note(request, check_case(method, wl, seed=int(T * 10)))
+
+
+# ----------------------------------------------------------------- general topology
+@pytest.mark.parametrize("method", ALL)
+def test_unbalanced_tree(method, request):
+    """first_child given: an unbalanced binary tree (left spine deeper than the right)."""
+    fc = [1, 3, -1, 5, -1, 7, -1, -1, -1]      # 0->(1,2) 1->(3,4) 3->(5,6) 5->(7,8)
+    N, k, depth, V, Bn = len(fc), 2, 5, 2500, 12
+    t, d = W.llm_like_logits(Bn, N, V, logit_std=3.0, draft_noise_std=1.0, dtype=torch.bfloat16, seed=21, device=DEV)
+    wl = W.Workload("unbalanced", Bn, N, V, k, depth, "bf16", "logits", 1.0, 1.0, t, d,
+                    first_child=torch.tensor(fc, dtype=torch.int32, device=DEV))
+    note(request, check_case(method, wl, seed=21))
+
+
+# ----------------------------------------------------------------- degenerate and invalid inputs
+def _tiny_probs(p_rows, q_rows, k=2, depth=2):
+    p = torch.tensor(p_rows, dtype=torch.float32, device=DEV).view(1, -1, len(p_rows[0]))
+    q = torch.tensor(q_rows, dtype=torch.float32, device=DEV).view(1, -1, len(q_rows[0]))
+    return B.Problem(p, q, B.PROBS, k, depth)
+
+
+def test_point_mass_draft_is_single_draft_case():
+    p = [[0.2, 0.5, 0.1, 0.2]] * 3
+    q = [[0.0, 1.0, 0.0, 0.0]] * 3
+    pb = _tiny_probs(p, q)
+    u_d = torch.tensor([[[0.4, 0.4]] * 3], dtype=torch.float32, device=DEV)
+    g = B.spechub_draft(pb, u_d)
+    assert _np(g["tokens"])[0].tolist() == [-1, 1, 1]
+    assert _np(g["flags"])[0, 0] & B.FLAG_DEGENERATE_HUB
+    for r0, want_oc, want_tok in ((0.49, 0, 1), (0.51, -1, None)):
+        u = torch.tensor([[[r0, 0.5, 0.55]] * 3], dtype=torch.float32, device=DEV)
+        v = B.spechub_verify(pb, g["tokens"], u, resid_mass=True)
+        assert _np(v["outcome"])[0, 0] == want_oc
+        o = oracle.spechub_verify(np.array(p[0]), np.array(q[0]), 1, 1, 1, r0, 0.5, float(np.float32(0.55)))
+        assert _np(v["token"])[0, 0] == o["token"]
+        assert _np(v["flags"])[0, 0] & B.FLAG_DEGENERATE_HUB
+        if want_tok is not None:
+            assert _np(v["token"])[0, 0] == want_tok
+
+
+def test_invalid_tokens_and_pairs_are_flagged():
+    p = [[0.2, 0.5, 0.3]] * 3
+    q = [[0.3, 0.4, 0.3]] * 3
+    pb = _tiny_probs(p, q)
+    u = torch.full((1, 3, 3), 0.5, dtype=torch.float32, device=DEV)
+    for toks, code, flag in (([-1, 0, 2], B.BAD_PAIR, B.FLAG_BAD_PAIR), ([-1, 7, 1], B.BAD_TOKEN, B.FLAG_BAD_TOKEN),
+                             ([-1, 1, 1], B.BAD_PAIR, B.FLAG_BAD_PAIR)):
+        t = torch.tensor([toks], dtype=torch.int32, device=DEV)
+        v = B.spechub_verify(pb, t, u)
+        assert _np(v["outcome"])[0, 0] == code and _np(v["flags"])[0, 0] & flag
+        assert _np(v["accept_depth"])[0] == 0
+    t = torch.tensor([[-1, 0, -5]], dtype=torch.int32, device=DEV)
+    for fn in (B.rrs_verify, B.rrsw_verify):
+        v = fn(pb, t, u)
+        assert _np(v["outcome"])[0, 0] == B.BAD_TOKEN
+
+
+@pytest.mark.parametrize("method", ["rrs", "rrsw"])
+def test_repeated_draft_tokens(method):
+    """Duplicates handed to the verifiers (RRS draws them; RRSw must treat the second as massless)."""
+    rng = np.random.default_rng(5)
+    V, k, depth = 40, 3, 2
+    N = W.tree_nodes(k, depth)
+    p = rng.dirichlet(np.full(V, 0.4), size=(6, N)).astype(np.float32)
+    q = rng.dirichlet(np.full(V, 0.4), size=(6, N)).astype(np.float32)
+    toks = np.full((6, N), -1, np.int32)
+    for b in range(6):
+        x = int(np.argmax(q[b, 0] - p[b, 0]))     # surely over-sampled: likely rejected
+        toks[b, 1:] = [x, x, (x + 1) % V]
+    u = np.full((6, N, k + 1), 0.97, np.float32)
+    pb = B.Problem(torch.from_numpy(p).to(DEV), torch.from_numpy(q).to(DEV), B.PROBS, k, depth)
+    g = {"rrs": B.rrs_verify, "rrsw": B.rrsw_verify}[method](pb, torch.from_numpy(toks).to(DEV),
+                                                              torch.from_numpy(u).to(DEV), resid_mass=True)
+    o = oracle.batch_verify(METHODS[method], p, q, toks, u, dtype=oracle.FP32, kind=oracle.PROBS, k=k, depth=depth)
+    near = o["margin"] < 1e-6
+    assert ((_np(g["outcome"]) == o["outcome"]) | near).all()
+    assert ((_np(g["token"]) == o["token"]) | near).all()
+
+
+# ----------------------------------------------------------------- determinism
+def test_bitwise_reproducible():
+    wl = W.config(3, device=DEV, B=8)
+    pb = B.Problem.from_workload(wl)
+    u_d = B.philox_uniform(3, 1, wl.B * wl.N, 2, device=DEV).view(wl.B, wl.N, 2)
+    u_v = B.philox_uniform(3, 2, wl.B * wl.N, 3, device=DEV).view(wl.B, wl.N, 3)
+    d1, d2 = B.spechub_draft(pb, u_d), B.spechub_draft(pb, u_d)
+    assert (d1["tokens"] == d2["tokens"]).all()
+    v1 = B.spechub_verify(pb, d1["tokens"], u_v, resid_mass=True)
+    v2 = B.spechub_verify(pb, d1["tokens"], u_v, resid_mass=True)
+    for key in v1:
+        assert torch.equal(v1[key], v2[key]), key
+
+
+# ----------------------------------------------------------------- Monte-Carlo tokens/step
+@pytest.mark.parametrize("method", ALL)
+def test_tokens_per_step_within_3_sigma(method, request):
+    """Batch efficiency (tokens per step = accept depth + 1, Sec. 5.3) of the GPU against the
+    oracle's on the same inputs, and both against each other's Monte-Carlo spread."""
+    wl = W.config(3, device=DEV, B=96, V=8000, seed=5)
+    pb = B.Problem.from_workload(wl)
+    from parity import DRAFT, VERIFY, uniforms, oracle_kwargs
+    from paper_2411_05289_amd.workloads import rows_as_numpy
+    u_d, u_v = uniforms(wl, 77)
+    g_d = DRAFT[method](pb, u_d)
+    g_v = VERIFY[method](pb, g_d["tokens"], u_v)
+    ok = oracle_kwargs(wl)
+    # an independent stream of uniforms for the oracle: a statistical, not bitwise, comparison
+    u_d2 = oracle.philox_uniform(78, 1, wl.B * wl.N, wl.k).reshape(wl.B, wl.N, wl.k)
+    u_v2 = oracle.philox_uniform(78, 2, wl.B * wl.N, wl.k + 1).reshape(wl.B, wl.N, wl.k + 1)
+    t_np, d_np = rows_as_numpy(wl.target), rows_as_numpy(wl.draft)
+    o_d = oracle.batch_draft(METHODS[method], d_np, u_d2, temp_draft=wl.temp_draft, nthreads=8, **ok)
+    o_v = oracle.batch_verify(METHODS[method], t_np, d_np, o_d["tokens"], u_v2, temp_target=wl.temp_target,
+                              temp_draft=wl.temp_draft, nthreads=8, **ok)
+    tg, to = _np(g_v["accept_depth"]) + 1.0, o_v["accept_depth"] + 1.0
+    sigma = np.sqrt(tg.var(ddof=1) / tg.size + to.var(ddof=1) / to.size)
+    note(request, dict(gpu=tokens_per_step(tg - 1), oracle=tokens_per_step(to - 1), sigma=float(sigma)))
+    assert abs(tg.mean() - to.mean()) < 3 * sigma

@@ -372,7 +372,8 @@ def test_toy_table_soft_pin():
             a = oracle.argmax(q)
             x = (a + 1) % 50
             acc_hub.append(1 - oracle.spechub_verify(p, q, a, x, a, 0.5, 0.5, 0.5)["resid_mass"])
-            m = oracle.rrs_verify(p, q, [0, 0], [ONE_MINUS, ONE_MINUS], 0.5)["mass"]
+            x = int(np.argmax(q - p))        # over-sampled: rejected by a uniform next to 1
+            m = oracle.rrs_verify(p, q, [x, x], [ONE_MINUS, ONE_MINUS], 0.5)["mass"]
             acc_rrs.append(1 - m[0] * m[1])
         # the table averages 100 pairs; allow 3 standard errors of such a mean
         se_rrs = np.std(acc_rrs) / 10
