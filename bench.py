@@ -1,0 +1,163 @@
+#!/usr/bin/env python3
+"""Benchmark of the sampling-verification hot path on one MI355X.
+
+A step = one pass of the whole path over one batch of synthetic token trees:
+spechub_draft (pair sampling for every internal node), spechub_verify (every
+node) and the tree walk.  Inputs are resident in HBM; the step rotates over
+several distinct copies of the batch so that the working set exceeds the
+256 MiB Infinity Cache and "HBM GB/s" is not cache bandwidth.
+
+Prints ONE JSON line (see the keys below).  --gpus above 1 is refused: this
+build runs on one GPU.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+METRIC = "verified tree nodes/sec and HBM GB/s (% peak) at V=32000, 31-node tree"
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--config", type=int, default=3, help="workload configuration 2..5 (3 = the metric's)")
+    ap.add_argument("--method", default="spechub", choices=["spechub", "rrs", "rrsw"])
+    ap.add_argument("--copies", type=int, default=0, help="distinct input copies to rotate over (0 = auto)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    return ap.parse_args()
+
+
+def read_traffic(kernel_key: str):
+    """HBM bytes per launch measured offline with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
+    kept as a small text summary under profiles/; None when no summary exists."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) >= 2 and f[0] == kernel_key:
+            return float(f[1])
+    return None
+
+
+def cpu_baseline(wl_cpu_rows, k, depth, temps, method_id, repeats, threads):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    import oracle
+    t_np, d_np = wl_cpu_rows
+    B, N, V = t_np.shape
+    u_d = oracle.philox_uniform(1, 1, B * N, k).reshape(B, N, k)
+    u_v = oracle.philox_uniform(1, 2, B * N, k + 1).reshape(B, N, k + 1)
+    kw = dict(dtype=oracle.BF16 if t_np.dtype == np.uint16 else oracle.FP32, kind=oracle.LOGITS, k=k,
+              depth=depth, nthreads=threads)
+    t0 = time.perf_counter()
+    for _ in range(repeats):
+        od = oracle.batch_draft(method_id, d_np, u_d, temp_draft=temps[1], **kw)
+        oracle.batch_verify(method_id, t_np, d_np, od["tokens"], u_v, temp_target=temps[0],
+                            temp_draft=temps[1], **kw)
+    dt = time.perf_counter() - t0
+    return B * N * repeats / dt, dt
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2411_05289_amd import binding as B
+    from paper_2411_05289_amd import workloads as W
+    if not torch.cuda.is_available():
+        print("bench.py needs the GPU: there is no CPU path", file=sys.stderr)
+        sys.exit(3)
+    B.lib()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    over = {}
+    if args.config == 5 and args.method == "spechub":
+        over = dict(k=2, depth=4)
+    wl0 = W.config(args.config, device=dev, seed=args.seed, **over)
+    alg_bytes = wl0.algorithmic_bytes()
+    copies = args.copies or max(2, -(-3 * 256 * 2 ** 20 // alg_bytes))   # >= 3x the Infinity Cache
+    if alg_bytes > 2 ** 30:
+        copies = args.copies or 2
+    wls = [wl0] + [W.config(args.config, device=dev, seed=args.seed + 1 + i, **over) for i in range(copies - 1)]
+    k, N, Bn = wl0.k, wl0.N, wl0.B
+    pbs = [B.Problem.from_workload(w) for w in wls]
+    u_d = [B.philox_uniform(args.seed + i, 1, Bn * N, k, device=dev).view(Bn, N, k) for i in range(copies)]
+    u_v = [B.philox_uniform(args.seed + i, 2, Bn * N, k + 1, device=dev).view(Bn, N, k + 1) for i in range(copies)]
+    plans = [B.StepPlan(args.method, pbs[i], u_d[i], u_v[i]) for i in range(copies)]
+    stream = B._stream()
+
+    def step(i, ev=None):
+        pl = plans[i % copies]
+        pl.draft(stream)
+        if ev is not None:
+            ev[0].record()
+        pl.verify(stream)
+        if ev is not None:
+            ev[1].record()
+        pl.walk(stream)
+        return pl.out["accept_depth"]
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ad = step(i, events[i])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    ms_per_step = 1e3 * dt / args.steps
+    nodes_per_s = Bn * N * args.steps / dt
+    kernel_ms = sum(e0.elapsed_time(e1) for e0, e1 in events) / args.steps
+    achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
+    tps = float(ad.float().mean().item()) + 1.0
+    kernel_key = "%s_verify:%s" % (args.method, wl0.name)
+
+    out = {
+        "metric": METRIC, "value": nodes_per_s, "unit": "nodes/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl0.name, "method": args.method, "B": Bn, "nodes_per_tree": N, "V": wl0.V,
+                   "k": k, "storage": wl0.dtype, "temperature": wl0.temp_target,
+                   "step": "draft+verify+walk", "input_copies_rotated": copies,
+                   "early_exit": True, "tokens_per_step_last_batch": tps},
+        "roofline": {"bound": "hbm", "kernel": "%s_verify" % args.method, "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": kernel_ms,
+                     "traffic": read_traffic(kernel_key)},
+    }
+    if not args.no_cpu_baseline:
+        threads = min(16, os.cpu_count() or 1)
+        sample_B = min(Bn, max(1, (64 * 32000) // wl0.V))     # about 2000 config-3-sized node rows
+        rows = (W.rows_as_numpy(wl0.target[:sample_B]), W.rows_as_numpy(wl0.draft[:sample_B]))
+        method_id = {"spechub": 0, "rrs": 1, "rrsw": 2}[args.method]
+        repeats = 8
+        v, secs = cpu_baseline(rows, k, wl0.depth, (wl0.temp_target, wl0.temp_draft), method_id, repeats, threads)
+        out["cpu_baseline"] = {"value": v, "unit": "nodes/s", "cores": threads, "kind": "oracle",
+                               "sample": "%d trees (%d nodes) of the same batch x %d repeats, %.1f s wall"
+                                         % (sample_B, sample_B * N, repeats, secs)}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -257,16 +257,80 @@ def rrsw_verify(pb: Problem, tokens, u, out=None, **want):
     return _verify("rrsw_verify", pb, tokens, u, out, **want)
 
 
-def tree_walk(pb: Problem, outcome, token):
+def tree_walk(pb: Problem, outcome, token, accept_depth=None, emitted=None):
     B, N, _ = pb.draft.shape
     cp = _c_problem(pb)
     dev = pb.draft.device
-    ad = torch.empty((B,), dtype=torch.int32, device=dev)
-    em = torch.empty((B, pb.depth), dtype=torch.int32, device=dev)
+    ad = torch.empty((B,), dtype=torch.int32, device=dev) if accept_depth is None else accept_depth
+    em = torch.empty((B, pb.depth), dtype=torch.int32, device=dev) if emitted is None else emitted
+    _check_dev(ad, "accept_depth", torch.int32, (B,))
+    _check_dev(em, "emitted", torch.int32, (B, pb.depth))
     rc = lib().mdsd_tree_walk(C.byref(cp), _ptr(outcome), _ptr(token), _ptr(ad), _ptr(em), _stream())
     if rc != 0:
         raise MdsdError(rc, "mdsd_tree_walk")
     return ad, em
+
+
+class StepPlan:
+    """Marshalled arguments of one draft + verify + walk step, so that a serving loop pays
+    three foreign calls per step and nothing else.  The tensors handed in must stay alive
+    and in place for the life of the plan."""
+
+    def __init__(self, method: str, pb: Problem, u_draft, u_verify, *, flags=True):
+        if method not in ("spechub", "rrs", "rrsw"):
+            raise ValueError("unknown method %r" % method)
+        B, N, _ = pb.draft.shape
+        dev = pb.draft.device
+        self.method, self.pb = method, pb
+        self._cp = _c_problem(pb)
+        _check_dev(u_draft, "u_draft", torch.float32, (B, N, pb.k))
+        _check_dev(u_verify, "u_verify", torch.float32, (B, N, pb.k + 1))
+        self.tokens = torch.empty((B, N), dtype=torch.int32, device=dev)
+        self.hub = torch.empty((B, N), dtype=torch.int32, device=dev)
+        self.draft_flags = torch.empty((B, N), dtype=torch.int32, device=dev)
+        self.out = alloc_result(pb, flags=flags, walk=True)
+        self._keep = (u_draft, u_verify)
+        res = _Result()
+        for name in ("outcome", "token", "flags"):
+            t = self.out.get(name)
+            setattr(res, name, None if t is None else t.data_ptr())
+        self._res = res          # no walk outputs: the walk is its own call below
+        L = lib()
+        pbp, resp = C.byref(self._cp), C.byref(res)
+        ud, uv = _ptr(u_draft), _ptr(u_verify)
+        tk, hb, df = _ptr(self.tokens), _ptr(self.hub), _ptr(self.draft_flags)
+        oc, tok = _ptr(self.out["outcome"]), _ptr(self.out["token"])
+        ad, em = _ptr(self.out["accept_depth"]), _ptr(self.out["emitted"])
+        if method == "spechub":
+            self._draft = lambda st: L.spechub_draft(pbp, ud, tk, hb, df, None, 0, st)
+        else:
+            fn = L.rrs_draft if method == "rrs" else L.rrsw_draft
+            self._draft = lambda st: fn(pbp, ud, tk, df, None, 0, st)
+        vfn = {"spechub": L.spechub_verify, "rrs": L.rrs_verify, "rrsw": L.rrsw_verify}[method]
+        self._verify = lambda st: vfn(pbp, tk, uv, resp, None, 0, st)
+        self._walk = lambda st: L.mdsd_tree_walk(pbp, oc, tok, ad, em, st)
+
+    def draft(self, stream=None):
+        rc = self._draft(_stream() if stream is None else stream)
+        if rc != 0:
+            raise MdsdError(rc, self.method + "_draft")
+
+    def verify(self, stream=None):
+        rc = self._verify(_stream() if stream is None else stream)
+        if rc != 0:
+            raise MdsdError(rc, self.method + "_verify")
+
+    def walk(self, stream=None):
+        rc = self._walk(_stream() if stream is None else stream)
+        if rc != 0:
+            raise MdsdError(rc, "mdsd_tree_walk")
+
+    def run(self, stream=None):
+        st = _stream() if stream is None else stream
+        self.draft(st)
+        self.verify(st)
+        self.walk(st)
+        return self.out
 
 
 def philox_uniform(seed: int, stream_id: int, rows: int, slots: int, device="cuda", want_words=False):

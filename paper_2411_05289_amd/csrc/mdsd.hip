@@ -81,76 +81,89 @@ __device__ __forceinline__ NodeId node_of_block(const Params& P)
 }
 
 // ---------------------------------------------------------------- passes
-// max of the stored values of one row
-template <int DT>
-__device__ __forceinline__ float lane_max1(const RowView& r)
+// max of the stored values this lane holds
+template <class Src>
+__device__ __forceinline__ float lane_max(const Src& src)
 {
-    constexpr int E = Elem<DT>::kPerChunk;
+    constexpr int E = Src::E;
     float m = -__builtin_inff();
-    slab_loop1<DT>(r, -__builtin_inff(), [&](int, int, const float(&a)[E]) {
+    src.for_each([&](int, int, const float(&a)[E]) {
 #pragma unroll
         for (int e = 0; e < E; ++e) m = fmaxf(m, a[e]);
     });
     return m;
 }
 
-// max of the stored values and the lowest index where this lane saw it
-template <int DT>
-__device__ __forceinline__ void lane_argmax1(const RowView& r, float& m, int& idx)
+// lowest virtual index at which this lane holds the value m (INT_MAX: nowhere)
+template <class Src>
+__device__ __forceinline__ int lane_first_index_of(const Src& src, float m)
 {
-    constexpr int E = Elem<DT>::kPerChunk;
-    m = -__builtin_inff();
-    idx = INT_MAX;
-    slab_loop1<DT>(r, -__builtin_inff(), [&](int, int chunk, const float(&a)[E]) {
+    constexpr int E = Src::E;
+    int idx = INT_MAX;
+    src.for_each([&](int, int chunk, const float(&a)[E]) {
 #pragma unroll
-        for (int e = 0; e < E; ++e)
-            if (a[e] > m) {
-                m = a[e];
-                idx = chunk * E + e;
-            }
+        for (int e = E - 1; e >= 0; --e)
+            if (a[e] == m) idx = min(idx, chunk * E + e);
     });
+    return idx;
 }
 
-// hub = lowest index among the maxima of the stored draft row (virtual index)
-template <int DT>
-__device__ __forceinline__ int block_argmax(const RowView& r, float& m_out, Shared& sh, int& phase)
+// hub = lowest index among the maxima of the stored draft row (virtual index).
+// Only lanes that hold the maximum look for its position.
+template <class Src>
+__device__ __forceinline__ int block_argmax(const Src& src, float m_lane, float m_block, Shared& sh,
+                                            int& phase)
 {
-    float m;
-    int idx;
-    lane_argmax1<DT>(r, m, idx);
-    float mm[1] = {m};
-    block_max<kWaves, 1>(mm, sh.red, phase);
-    m_out = mm[0];
-    const int a = block_min_index<kWaves>(m == mm[0] ? idx : INT_MAX, sh.red, phase);
-    return a == INT_MAX ? r.head : a;  // a row of NaNs has no maximum: stay in bounds
+    int idx = INT_MAX;
+    if (m_lane == m_block) idx = lane_first_index_of(src, m_block);
+    const int a = block_min_index<kWaves>(idx, sh.red, phase);
+    return a == INT_MAX ? src.r.head : a;  // a row of NaNs has no maximum: stay in bounds
 }
 
-// sum of the weights of one row with one slab sum per slab left in LDS;
-// elements whose virtual index is in excl[0..n_excl) count as 0
-template <int DT, bool LOGITS>
-__device__ __forceinline__ void pass_weights_to_slabs(const RowView& r, ToWeight<LOGITS> cv,
-                                                      const int* excl, int n_excl, float* slab_w)
+// zero the entries of one chunk whose virtual index is listed in excl
+template <int E>
+__device__ __forceinline__ void zero_excluded(float (&w)[E], int chunk, const int* excl, int n_excl)
 {
-    constexpr int E = Elem<DT>::kPerChunk;
-    slab_loop1<DT>(r, ToWeight<LOGITS>::fill(), [&](int s, int chunk, const float(&a)[E]) {
+    for (int j = 0; j < n_excl; ++j) {
+        const int off = excl[j] - chunk * E;
+        if (off >= 0 && off < E) {
+#pragma unroll
+            for (int e = 0; e < E; ++e)
+                if (e == off) w[e] = 0.f;
+        }
+    }
+}
+
+// slab holds one of the excluded elements?
+template <int E>
+__device__ __forceinline__ bool slab_has_excluded(int s, const int* excl, int n_excl)
+{
+    bool hit = false;
+    for (int j = 0; j < n_excl; ++j) hit = hit || (excl[j] / (64 * E) == s);
+    return hit;
+}
+
+// weights of one row, one slab sum per slab left in LDS; elements listed in
+// excl count as 0
+template <bool LOGITS, class Src>
+__device__ __forceinline__ void pass_weights_to_slabs(const Src& src, ToWeight<LOGITS> cv, const int* excl,
+                                                      int n_excl, float* slab_w)
+{
+    constexpr int E = Src::E;
+    src.for_each([&](int s, int chunk, const float(&a)[E]) {
         float w[E];
 #pragma unroll
         for (int e = 0; e < E; ++e) w[e] = cv(a[e]);
-        for (int j = 0; j < n_excl; ++j)
-            if (excl[j] / (64 * E) == s) {
-#pragma unroll
-                for (int e = 0; e < E; ++e)
-                    if (chunk * E + e == excl[j]) w[e] = 0.f;
-            }
+        if (slab_has_excluded<E>(s, excl, n_excl)) zero_excluded<E>(w, chunk, excl, n_excl);
         store_slab_sum(slab_w, s, chunk_sum<E>(w));
     });
 }
 
-// this lane's chunk of slab s of the same weights (for the draw inside a slab)
+// this lane's chunk of slab s of the same weights, read from memory (the draw
+// inside one slab; the slab index is only known at run time)
 template <int DT, bool LOGITS>
-__device__ __forceinline__ void chunk_weights(const RowView& r, ToWeight<LOGITS> cv,
-                                              const int* excl, int n_excl, int s,
-                                              float (&w)[Elem<DT>::kPerChunk])
+__device__ __forceinline__ void chunk_weights(const RowView& r, ToWeight<LOGITS> cv, const int* excl,
+                                              int n_excl, int s, float (&w)[Elem<DT>::kPerChunk])
 {
     constexpr int E = Elem<DT>::kPerChunk;
     const int chunk = s * 64 + (threadIdx.x & 63);
@@ -158,18 +171,13 @@ __device__ __forceinline__ void chunk_weights(const RowView& r, ToWeight<LOGITS>
     load_chunk<DT>(r, chunk, ToWeight<LOGITS>::fill(), a);
 #pragma unroll
     for (int e = 0; e < E; ++e) w[e] = cv(a[e]);
-    for (int j = 0; j < n_excl; ++j) {
-#pragma unroll
-        for (int e = 0; e < E; ++e)
-            if (chunk * E + e == excl[j]) w[e] = 0.f;
-    }
+    zero_excluded<E>(w, chunk, excl, n_excl);
 }
 
 // Draw from the weights of one row (slab sums already in LDS and visible).
 template <int DT, bool LOGITS>
-__device__ __forceinline__ int draw_from_row(const RowView& r, ToWeight<LOGITS> cv,
-                                             const int* excl, int n_excl, const float* slab_w,
-                                             float u, float& W)
+__device__ __forceinline__ int draw_from_row(const RowView& r, ToWeight<LOGITS> cv, const int* excl,
+                                             int n_excl, const float* slab_w, float u, float& W)
 {
     constexpr int E = Elem<DT>::kPerChunk;
     auto sv = [&](int i) { return slab_w[i]; };
@@ -199,9 +207,8 @@ __device__ __forceinline__ void spechub_terms(float ep, float eq, const HubScal&
 }
 
 template <int DT, bool LOGITS>
-__device__ __forceinline__ void spechub_chunk_w(const RowView& rp, const RowView& rq,
-                                                ToWeight<LOGITS> cp, ToWeight<LOGITS> cq,
-                                                const HubScal& h, int a_virt, int s,
+__device__ __forceinline__ void spechub_chunk_w(const RowView& rp, const RowView& rq, ToWeight<LOGITS> cp,
+                                                ToWeight<LOGITS> cq, const HubScal& h, int a_virt, int s,
                                                 float (&w)[Elem<DT>::kPerChunk])
 {
     constexpr int E = Elem<DT>::kPerChunk;
@@ -225,10 +232,9 @@ __device__ __forceinline__ float rrs_term(float ep, float eq, float iZp, float c
 }
 
 template <int DT, bool LOGITS>
-__device__ __forceinline__ void rrs_chunk_w(const RowView& rp, const RowView& rq,
-                                            ToWeight<LOGITS> cp, ToWeight<LOGITS> cq, float iZp,
-                                            float c_iZq, const int* excl, int n_excl, int s,
-                                            float (&w)[Elem<DT>::kPerChunk])
+__device__ __forceinline__ void rrs_chunk_w(const RowView& rp, const RowView& rq, ToWeight<LOGITS> cp,
+                                            ToWeight<LOGITS> cq, float iZp, float c_iZq, const int* excl,
+                                            int n_excl, int s, float (&w)[Elem<DT>::kPerChunk])
 {
     constexpr int E = Elem<DT>::kPerChunk;
     const int chunk = s * 64 + (threadIdx.x & 63);
@@ -237,11 +243,7 @@ __device__ __forceinline__ void rrs_chunk_w(const RowView& rp, const RowView& rq
     load_chunk<DT>(rq, chunk, ToWeight<LOGITS>::fill(), b);
 #pragma unroll
     for (int e = 0; e < E; ++e) w[e] = rrs_term(cp(a[e]), cq(b[e]), iZp, c_iZq);
-    for (int j = 0; j < n_excl; ++j) {
-#pragma unroll
-        for (int e = 0; e < E; ++e)
-            if (chunk * E + e == excl[j]) w[e] = 0.f;
-    }
+    zero_excluded<E>(w, chunk, excl, n_excl);
 }
 
 // write norm(w) of a whole row (diagnostic output)
@@ -264,11 +266,12 @@ __device__ __forceinline__ void write_resid_prob(float* out, const RowView& r, f
 }
 
 // ---------------------------------------------------------------- verify kernel
-template <int DT, bool LOGITS, int METHOD>
+template <int DT, bool LOGITS, int METHOD, int NIT>
 __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
 {
     constexpr int E = Elem<DT>::kPerChunk;
     using CV = ToWeight<LOGITS>;
+    using Src = RowSrc<DT, NIT>;
     __shared__ Shared sh;
     int phase = 0;
     const NodeId id = node_of_block(P);
@@ -278,6 +281,8 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
     float* rprob = P.resid_prob ? P.resid_prob + id.row * (int64_t)P.V : nullptr;
 
     const RowView rp = make_row<DT>(P.target, P.ld_t, id.row, P.V);
+    Src sp;
+    sp.init(rp, CV::fill());
     int outcome = MDSD_NONE, token = -1, flags = 0;
     float rmass = 0.f;
 
@@ -285,12 +290,12 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
         // ---- leaf: the k = 0 case of Alg. 1, token ~ p
         CV cp{0.f, 0.f};
         if constexpr (LOGITS) {
-            float mm[1] = {lane_max1<DT>(rp)};
+            float mm[1] = {lane_max(sp)};
             block_max<kWaves, 1>(mm, sh.red, phase);
             cp.s = kLog2e / P.temp_target;
             cp.ms = mm[0] * cp.s;
         }
-        pass_weights_to_slabs<DT, LOGITS>(rp, cp, nullptr, 0, sh.slab_w);
+        pass_weights_to_slabs<LOGITS>(sp, cp, nullptr, 0, sh.slab_w);
         __syncthreads();
         float W;
         const int v = draw_from_row<DT, LOGITS>(rp, cp, nullptr, 0, sh.slab_w, ur[k], W);
@@ -303,32 +308,35 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
             });
     } else {
         const RowView rq = make_row<DT>(P.draft, P.ld_d, id.row, P.V);
+        Src sq;
+        sq.init(rq, CV::fill());
         const int32_t* xt = P.tokens + (int64_t)id.b * P.N + id.c0;
         CV cp{0.f, 0.f}, cq{0.f, 0.f};
 
         if constexpr (METHOD == kSpecHub) {
-            // ---- hub and softmax maxima
-            float mq;
-            const int a_virt = block_argmax<DT>(rq, mq, sh, phase);
+            // ---- hub (argmax of the stored draft row) and softmax maxima
+            const float mq_lane = lane_max(sq);
+            float mm[2] = {LOGITS ? lane_max(sp) : 0.f, mq_lane};
+            block_max<kWaves, 2>(mm, sh.red, phase);
+            const int a_virt = block_argmax(sq, mq_lane, mm[1], sh, phase);
             const int a = a_virt - rq.head;
             if constexpr (LOGITS) {
-                float mm[1] = {lane_max1<DT>(rp)};
-                block_max<kWaves, 1>(mm, sh.red, phase);
                 cp.s = kLog2e / P.temp_target;
                 cp.ms = mm[0] * cp.s;
                 cq.s = kLog2e / P.temp_draft;
-                cq.ms = mq * cq.s;
+                cq.ms = mm[1] * cq.s;
             }
             // ---- normalisers: Zp (logits only) and D-part Zq' = sum_{y != a} eq
+            const int a_slab = a_virt / (64 * E);
             float z[2] = {0.f, 0.f};
-            slab_loop2<DT>(rp, rq, CV::fill(), [&](int, int chunk, const float(&pa)[E], const float(&qa)[E]) {
+            for_each2<DT, NIT>(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
                 float wp[E], wq[E];
 #pragma unroll
                 for (int e = 0; e < E; ++e) {
-                    wp[e] = cp(pa[e]);
-                    wq[e] = cq(qa[e]);
-                    if (chunk * E + e == a_virt) wq[e] = 0.f;
+                    wp[e] = cp(pa_[e]);
+                    wq[e] = cq(qa_[e]);
                 }
+                if (s == a_slab) zero_excluded<E>(wq, chunk, &a_virt, 1);
                 z[0] += chunk_sum<E>(wp);
                 z[1] += chunk_sum<E>(wq);
             });
@@ -389,7 +397,7 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
             if (!decided || need_full) {
                 if (degenerate) {
                     // residual of the single-draft case: p with the hub removed
-                    pass_weights_to_slabs<DT, LOGITS>(rp, cp, &a_virt, 1, sh.slab_w);
+                    pass_weights_to_slabs<LOGITS>(sp, cp, &a_virt, 1, sh.slab_w);
                     __syncthreads();
                     float W;
                     const int v = draw_from_row<DT, LOGITS>(rp, cp, &a_virt, 1, sh.slab_w, ur[2], W);
@@ -405,15 +413,19 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
                 } else {
                     // ---- residual sums: S_xa = sum Q'(.,a), S_ax = sum Q'(a,.), slab sums of p''
                     float sacc[2] = {0.f, 0.f};
-                    slab_loop2<DT>(rp, rq, CV::fill(),
-                                   [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
-                        float t_xa[E], t_ax[E], w[E];
+                    for_each2<DT, NIT>(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
+                        float ep[E], eq[E], t_xa[E], t_ax[E], w[E];
 #pragma unroll
                         for (int e = 0; e < E; ++e) {
-                            float ep = cp(pa_[e]), eq = cq(qa_[e]);
-                            if (chunk * E + e == a_virt) ep = eq = 0.f;
-                            spechub_terms(ep, eq, h, t_xa[e], t_ax[e], w[e]);
+                            ep[e] = cp(pa_[e]);
+                            eq[e] = cq(qa_[e]);
                         }
+                        if (s == a_slab) {
+                            zero_excluded<E>(ep, chunk, &a_virt, 1);
+                            zero_excluded<E>(eq, chunk, &a_virt, 1);
+                        }
+#pragma unroll
+                        for (int e = 0; e < E; ++e) spechub_terms(ep[e], eq[e], h, t_xa[e], t_ax[e], w[e]);
                         sacc[0] += chunk_sum<E>(t_xa);
                         sacc[1] += chunk_sum<E>(t_ax);
                         store_slab_sum(sh.slab_w, s, chunk_sum<E>(w));
@@ -449,7 +461,7 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
                             // no residual mass: fall back to p itself
                             flags |= MDSD_FLAG_ZERO_RESIDUAL;
                             __syncthreads();
-                            pass_weights_to_slabs<DT, LOGITS>(rp, cp, nullptr, 0, sh.slab_w);
+                            pass_weights_to_slabs<LOGITS>(sp, cp, nullptr, 0, sh.slab_w);
                             __syncthreads();
                             float Wp;
                             v = draw_from_row<DT, LOGITS>(rp, cp, nullptr, 0, sh.slab_w, ur[2], Wp);
@@ -479,7 +491,7 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
                 outcome = MDSD_BAD_TOKEN;
             } else {
                 if constexpr (LOGITS) {
-                    float mm[2] = {lane_max1<DT>(rp), lane_max1<DT>(rq)};
+                    float mm[2] = {lane_max(sp), lane_max(sq)};
                     block_max<kWaves, 2>(mm, sh.red, phase);
                     cp.s = kLog2e / P.temp_target;
                     cp.ms = mm[0] * cp.s;
@@ -497,7 +509,7 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
                 // normalisers; without replacement the draft sum leaves out every draft token,
                 // so that the mass remaining after i removals is a sum of positive terms
                 float z[2] = {0.f, 0.f};
-                slab_loop2<DT>(rp, rq, CV::fill(), [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
+                for_each2<DT, NIT>(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
                     float wp[E], wq[E];
 #pragma unroll
                     for (int e = 0; e < E; ++e) {
@@ -505,12 +517,7 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
                         wq[e] = cq(qa_[e]);
                     }
                     if constexpr (WO) {
-                        for (int j = 0; j < k; ++j)
-                            if (xv[j] / (64 * E) == s) {
-#pragma unroll
-                                for (int e = 0; e < E; ++e)
-                                    if (chunk * E + e == xv[j]) wq[e] = 0.f;
-                            }
+                        if (slab_has_excluded<E>(s, xv, k)) zero_excluded<E>(wq, chunk, xv, k);
                     }
                     z[0] += chunk_sum<E>(wp);
                     z[1] += chunk_sum<E>(wq);
@@ -528,9 +535,9 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
                 float c = 0.f, Wc = 1.f;
                 float slab_c = -1.f;  // c of the slab sums in LDS (-1: none)
                 int slab_nx = -1;
-                bool decided = false, exhausted = false;
+                bool decided = false;
                 int n_rej = 0;  // tokens xs[0..n_rej) have been rejected
-                for (int i = 0; i < k && !exhausted; ++i) {
+                for (int i = 0; i < k; ++i) {
                     const float px = cp(load_elem<DT>(rp, xs[i])) * iZp;
                     const float qx = eqx[i] * iZq;
                     // draft probability of x_i in this round and the factor rho that rescales q;
@@ -554,16 +561,11 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
                     n_rej = i + 1;
                     if (i > 0) __syncthreads();  // earlier readers of slab_w are done
                     const float c_iZq = c_new * iZq;
-                    slab_loop2<DT>(rp, rq, CV::fill(), [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
+                    for_each2<DT, NIT>(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
                         float w[E];
 #pragma unroll
                         for (int e = 0; e < E; ++e) w[e] = rrs_term(cp(pa_[e]), cq(qa_[e]), iZp, c_iZq);
-                        for (int j = 0; j < n_rej; ++j)
-                            if (xv[j] / (64 * E) == s) {
-#pragma unroll
-                                for (int e = 0; e < E; ++e)
-                                    if (chunk * E + e == xv[j]) w[e] = 0.f;
-                            }
+                        if (slab_has_excluded<E>(s, xv, n_rej)) zero_excluded<E>(w, chunk, xv, n_rej);
                         store_slab_sum(sh.slab_w, s, chunk_sum<E>(w));
                     });
                     __syncthreads();
@@ -580,7 +582,7 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
                     if constexpr (WO) {
                         if (!(rem[i + 1] > 0.f)) {
                             flags |= MDSD_FLAG_Q_EXHAUSTED;
-                            exhausted = true;
+                            break;
                         }
                     }
                 }
@@ -590,14 +592,16 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
                         rrs_chunk_w<DT, LOGITS>(rp, rq, cp, cq, iZp, c_iZq, xv, n_rej, s, w);
                     };
                     if (slab_c != c || slab_nx != n_rej) {
-                        // slab sums in LDS are not those of the current residual (k == 0 cannot
-                        // happen here; a round without mass can): rebuild them
+                        // the slab sums in LDS are not those of the current residual (accepted in
+                        // the first round, or a round without mass): rebuild them
                         __syncthreads();
-                        for (int s = threadIdx.x >> 6; s < rp.nslab; s += kWaves) {
+                        for_each2<DT, NIT>(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
                             float w[E];
-                            cw(s, w);
+#pragma unroll
+                            for (int e = 0; e < E; ++e) w[e] = rrs_term(cp(pa_[e]), cq(qa_[e]), iZp, c_iZq);
+                            if (slab_has_excluded<E>(s, xv, n_rej)) zero_excluded<E>(w, chunk, xv, n_rej);
                             store_slab_sum(sh.slab_w, s, chunk_sum<E>(w));
-                        }
+                        });
                         __syncthreads();
                     }
                     auto sv = [&](int j) { return sh.slab_w[j]; };
@@ -623,7 +627,7 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
 }
 
 // ---------------------------------------------------------------- draft kernel
-template <int DT, bool LOGITS, int METHOD>
+template <int DT, bool LOGITS, int METHOD, int NIT>
 __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
 {
     constexpr int E = Elem<DT>::kPerChunk;
@@ -645,17 +649,24 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
     const int k = P.k;
     const float* ur = P.u + row * k;
     const RowView rq = make_row<DT>(P.draft, P.ld_d, row, P.V);
+    RowSrc<DT, NIT> sq;
+    sq.init(rq, CV::fill());
     int32_t* xt = P.tokens_out + (int64_t)b * P.N + c0;
     int flags = 0;
 
     CV cq{0.f, 0.f};
-    float mq;
-    const int a_virt = block_argmax<DT>(rq, mq, sh, phase);
-    if constexpr (LOGITS) {
-        cq.s = kLog2e / P.temp_draft;
-        cq.ms = mq * cq.s;
+    int a_virt = rq.head;
+    if (LOGITS || METHOD == kSpecHub) {
+        const float mq_lane = lane_max(sq);
+        float mm[1] = {mq_lane};
+        block_max<kWaves, 1>(mm, sh.red, phase);
+        if constexpr (METHOD == kSpecHub) a_virt = block_argmax(sq, mq_lane, mm[0], sh, phase);
+        if constexpr (LOGITS) {
+            cq.s = kLog2e / P.temp_draft;
+            cq.ms = mm[0] * cq.s;
+        }
     }
-    pass_weights_to_slabs<DT, LOGITS>(rq, cq, nullptr, 0, sh.slab_w);
+    pass_weights_to_slabs<LOGITS>(sq, cq, nullptr, 0, sh.slab_w);
     __syncthreads();
 
     // slab sums with some tokens removed: only the slabs holding a removed token change,
@@ -849,21 +860,57 @@ static int validate(const mdsd_problem* pb, int method, bool need_target, Params
     return MDSD_OK;
 }
 
+// chunks per lane that hold a whole row in registers; 0 = stream the row in every pass
+static int resident_chunks(const mdsd_problem* pb)
+{
+    const int per_chunk = pb->dtype == MDSD_FP32 ? 4 : 8;
+    // worst case head of per_chunk - 1 masked elements in front of the row
+    const int64_t nchunk = ((int64_t)pb->V + 2 * per_chunk - 2) / per_chunk;
+    const int64_t per_lane = (nchunk + kWG - 1) / kWG;
+    if (per_lane <= 4) return 4;
+    if (per_lane <= 8) return 8;
+    if (per_lane <= 16) return 16;
+    return 0;
+}
+
+template <int DT, bool LG, int METHOD>
+static void launch_verify_n(int nit, dim3 grid, dim3 block, hipStream_t st, const Params& P)
+{
+    switch (nit) {
+    case 4: hipLaunchKernelGGL((verify_kernel<DT, LG, METHOD, 4>), grid, block, 0, st, P); break;
+    case 8: hipLaunchKernelGGL((verify_kernel<DT, LG, METHOD, 8>), grid, block, 0, st, P); break;
+    case 16: hipLaunchKernelGGL((verify_kernel<DT, LG, METHOD, 16>), grid, block, 0, st, P); break;
+    default: hipLaunchKernelGGL((verify_kernel<DT, LG, METHOD, 0>), grid, block, 0, st, P); break;
+    }
+}
+
 template <int METHOD>
 static void launch_verify(const mdsd_problem* pb, const Params& P, hipStream_t st)
 {
     const dim3 grid((unsigned)(P.B * P.N)), block(kWG);
     const bool lg = pb->kind == MDSD_LOGITS;
+    const int nit = resident_chunks(pb);
     if (pb->dtype == MDSD_FP32) {
         if (lg)
-            hipLaunchKernelGGL((verify_kernel<0, true, METHOD>), grid, block, 0, st, P);
+            launch_verify_n<0, true, METHOD>(nit, grid, block, st, P);
         else
-            hipLaunchKernelGGL((verify_kernel<0, false, METHOD>), grid, block, 0, st, P);
+            launch_verify_n<0, false, METHOD>(nit, grid, block, st, P);
     } else {
         if (lg)
-            hipLaunchKernelGGL((verify_kernel<1, true, METHOD>), grid, block, 0, st, P);
+            launch_verify_n<1, true, METHOD>(nit, grid, block, st, P);
         else
-            hipLaunchKernelGGL((verify_kernel<1, false, METHOD>), grid, block, 0, st, P);
+            launch_verify_n<1, false, METHOD>(nit, grid, block, st, P);
+    }
+}
+
+template <int DT, bool LG, int METHOD>
+static void launch_draft_n(int nit, dim3 grid, dim3 block, hipStream_t st, const Params& P)
+{
+    switch (nit) {
+    case 4: hipLaunchKernelGGL((draft_kernel<DT, LG, METHOD, 4>), grid, block, 0, st, P); break;
+    case 8: hipLaunchKernelGGL((draft_kernel<DT, LG, METHOD, 8>), grid, block, 0, st, P); break;
+    case 16: hipLaunchKernelGGL((draft_kernel<DT, LG, METHOD, 16>), grid, block, 0, st, P); break;
+    default: hipLaunchKernelGGL((draft_kernel<DT, LG, METHOD, 0>), grid, block, 0, st, P); break;
     }
 }
 
@@ -872,16 +919,17 @@ static void launch_draft(const mdsd_problem* pb, const Params& P, hipStream_t st
 {
     const dim3 grid((unsigned)(P.B * P.N)), block(kWG);
     const bool lg = pb->kind == MDSD_LOGITS;
+    const int nit = resident_chunks(pb);
     if (pb->dtype == MDSD_FP32) {
         if (lg)
-            hipLaunchKernelGGL((draft_kernel<0, true, METHOD>), grid, block, 0, st, P);
+            launch_draft_n<0, true, METHOD>(nit, grid, block, st, P);
         else
-            hipLaunchKernelGGL((draft_kernel<0, false, METHOD>), grid, block, 0, st, P);
+            launch_draft_n<0, false, METHOD>(nit, grid, block, st, P);
     } else {
         if (lg)
-            hipLaunchKernelGGL((draft_kernel<1, true, METHOD>), grid, block, 0, st, P);
+            launch_draft_n<1, true, METHOD>(nit, grid, block, st, P);
         else
-            hipLaunchKernelGGL((draft_kernel<1, false, METHOD>), grid, block, 0, st, P);
+            launch_draft_n<1, false, METHOD>(nit, grid, block, st, P);
     }
 }
 

@@ -15,7 +15,10 @@
 
 namespace mdsd {
 
-constexpr int kWG = 256;
+#ifndef MDSD_WG
+#define MDSD_WG 512
+#endif
+constexpr int kWG = MDSD_WG;
 constexpr int kWaves = kWG / kWave;
 constexpr int kMaxSlabs = 2048;
 constexpr float kLog2e = 1.44269504088896340736f;
@@ -49,31 +52,114 @@ __device__ __forceinline__ float chunk_sum(const float (&w)[E])
         return (w[0] + w[1]) + (w[2] + w[3]);
 }
 
-// body(slab, chunk, a[E])           for one row
-template <int DT, class Body>
-__device__ __forceinline__ void slab_loop1(const RowView& ra, float fill, Body body)
-{
-    constexpr int E = Elem<DT>::kPerChunk;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int s = wave; s < ra.nslab; s += kWaves) {
-        float a[E];
-        load_chunk<DT>(ra, s * 64 + lane, fill, a);
-        body(s, s * 64 + lane, a);
-    }
-}
+// A row as the passes see it.  NIT == 0: every pass streams the row from memory
+// (any V).  NIT > 0: the row is loaded once, NIT chunks per lane, and stays in
+// registers for all passes (V up to NIT * kWaves * 64 chunks); chunk `it` of a
+// lane belongs to slab it * kWaves + wave, so each load instruction of a wave
+// still covers 1 KiB of consecutive memory.  Masked elements hold `fill`.
+template <int DT, int NIT>
+struct RowSrc {
+    static constexpr int E = Elem<DT>::kPerChunk;
+    RowView r;
+    uint4 d[NIT];
 
-// body(slab, chunk, a[E], b[E])     for two rows with the same head
-template <int DT, class Body>
-__device__ __forceinline__ void slab_loop2(const RowView& ra, const RowView& rb, float fill,
-                                           Body body)
+    __device__ __forceinline__ void init(const RowView& rv, float fill)
+    {
+        r = rv;
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const uint32_t fb = __builtin_bit_cast(uint32_t, fill);
+        const uint32_t fw = DT == 0 ? fb : ((fb >> 16) | (fb & 0xffff0000u));
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int chunk = (it * kWaves + wave) * 64 + lane;
+            d[it] = chunk < r.nchunk ? r.chunks[chunk] : make_uint4(fw, fw, fw, fw);
+        }
+        // the first and the last chunk of the row may hold elements that are not the row's
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int chunk = (it * kWaves + wave) * 64 + lane;
+            const int v0 = chunk * E;
+            if (chunk < r.nchunk && (v0 < r.head || v0 + E > r.nvirt)) {
+                float v[E];
+                unpack<DT>(d[it], v);
+                uint32_t w[E];
+#pragma unroll
+                for (int e = 0; e < E; ++e)
+                    w[e] = (v0 + e < r.head || v0 + e >= r.nvirt) ? fb : __builtin_bit_cast(uint32_t, v[e]);
+                if constexpr (DT == 0)
+                    d[it] = make_uint4(w[0], w[1], w[2], w[3]);
+                else
+                    d[it] = make_uint4((w[0] >> 16) | (w[1] & 0xffff0000u), (w[2] >> 16) | (w[3] & 0xffff0000u),
+                                       (w[4] >> 16) | (w[5] & 0xffff0000u), (w[6] >> 16) | (w[7] & 0xffff0000u));
+            }
+        }
+    }
+
+    // body(slab, chunk, a[E])
+    template <class Body>
+    __device__ __forceinline__ void for_each(Body body) const
+    {
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int s = it * kWaves + wave;
+            if (s < r.nslab) {
+                float a[E];
+                unpack<DT>(d[it], a);
+                body(s, s * 64 + lane, a);
+            }
+        }
+    }
+};
+
+template <int DT>
+struct RowSrc<DT, 0> {
+    static constexpr int E = Elem<DT>::kPerChunk;
+    RowView r;
+    float fill;
+
+    __device__ __forceinline__ void init(const RowView& rv, float f)
+    {
+        r = rv;
+        fill = f;
+    }
+
+    template <class Body>
+    __device__ __forceinline__ void for_each(Body body) const
+    {
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        for (int s = wave; s < r.nslab; s += kWaves) {
+            float a[E];
+            load_chunk<DT>(r, s * 64 + lane, fill, a);
+            body(s, s * 64 + lane, a);
+        }
+    }
+};
+
+// body(slab, chunk, a[E], b[E]) over two rows with the same head and length
+template <int DT, int NIT, class Body>
+__device__ __forceinline__ void for_each2(const RowSrc<DT, NIT>& sa, const RowSrc<DT, NIT>& sb, Body body)
 {
     constexpr int E = Elem<DT>::kPerChunk;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int s = wave; s < ra.nslab; s += kWaves) {
-        float a[E], b[E];
-        load_chunk<DT>(ra, s * 64 + lane, fill, a);
-        load_chunk<DT>(rb, s * 64 + lane, fill, b);
-        body(s, s * 64 + lane, a, b);
+    if constexpr (NIT == 0) {
+        for (int s = wave; s < sa.r.nslab; s += kWaves) {
+            float a[E], b[E];
+            load_chunk<DT>(sa.r, s * 64 + lane, sa.fill, a);
+            load_chunk<DT>(sb.r, s * 64 + lane, sb.fill, b);
+            body(s, s * 64 + lane, a, b);
+        }
+    } else {
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int s = it * kWaves + wave;
+            if (s < sa.r.nslab) {
+                float a[E], b[E];
+                unpack<DT>(sa.d[it], a);
+                unpack<DT>(sb.d[it], b);
+                body(s, s * 64 + lane, a, b);
+            }
+        }
     }
 }
 
