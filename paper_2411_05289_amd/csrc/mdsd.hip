@@ -12,9 +12,11 @@
 // Scalar look-ups of p(x), q(x) at the draft tokens sit between them.
 #include <hip/hip_runtime.h>
 #include <limits.h>
+#include <stdlib.h>
 #include <stdint.h>
 
 #include "mdsd.h"
+#include "resident.h"
 #include "scan_core.h"
 
 namespace mdsd {
@@ -43,6 +45,8 @@ struct Params {
 struct Shared {
     BlockScratch<kWaves> red;
     float slab_w[kMaxSlabs];
+    float bcast_f;  // one value handed from one lane to the workgroup
+    int bcast_i;
 };
 
 // Node of this workgroup.  Complete trees: nodes with children first (they
@@ -52,10 +56,9 @@ struct NodeId {
     int64_t row;
 };
 
-__device__ __forceinline__ NodeId node_of_block(const Params& P)
+__device__ __forceinline__ NodeId node_of_item(const Params& P, int w)
 {
     NodeId id;
-    int w = blockIdx.x;
     if (P.first_child == nullptr) {
         const int total_int = P.B * P.n_internal;
         if (w < total_int) {
@@ -79,6 +82,8 @@ __device__ __forceinline__ NodeId node_of_block(const Params& P)
     id.row = (int64_t)id.b * P.N + id.n;
     return id;
 }
+
+__device__ __forceinline__ NodeId node_of_block(const Params& P) { return node_of_item(P, blockIdx.x); }
 
 // ---------------------------------------------------------------- passes
 // max of the stored values this lane holds
@@ -145,9 +150,9 @@ __device__ __forceinline__ bool slab_has_excluded(int s, const int* excl, int n_
 
 // weights of one row, one slab sum per slab left in LDS; elements listed in
 // excl count as 0
-template <bool LOGITS, class Src>
-__device__ __forceinline__ void pass_weights_to_slabs(const Src& src, ToWeight<LOGITS> cv, const int* excl,
-                                                      int n_excl, float* slab_w)
+template <class CV, class Src>
+__device__ __forceinline__ void pass_weights_to_slabs(const Src& src, CV cv, const int* excl, int n_excl,
+                                                      float* slab_w)
 {
     constexpr int E = Src::E;
     src.for_each([&](int s, int chunk, const float(&a)[E]) {
@@ -161,29 +166,29 @@ __device__ __forceinline__ void pass_weights_to_slabs(const Src& src, ToWeight<L
 
 // this lane's chunk of slab s of the same weights, read from memory (the draw
 // inside one slab; the slab index is only known at run time)
-template <int DT, bool LOGITS>
-__device__ __forceinline__ void chunk_weights(const RowView& r, ToWeight<LOGITS> cv, const int* excl,
-                                              int n_excl, int s, float (&w)[Elem<DT>::kPerChunk])
+template <int DT, class CV>
+__device__ __forceinline__ void chunk_weights(const RowView& r, CV cv, const int* excl, int n_excl, int s,
+                                              float (&w)[Elem<DT>::kPerChunk])
 {
     constexpr int E = Elem<DT>::kPerChunk;
     const int chunk = s * 64 + (threadIdx.x & 63);
     float a[E];
-    load_chunk<DT>(r, chunk, ToWeight<LOGITS>::fill(), a);
+    load_chunk<DT>(r, chunk, CV::fill(), a);
 #pragma unroll
     for (int e = 0; e < E; ++e) w[e] = cv(a[e]);
     zero_excluded<E>(w, chunk, excl, n_excl);
 }
 
 // Draw from the weights of one row (slab sums already in LDS and visible).
-template <int DT, bool LOGITS>
-__device__ __forceinline__ int draw_from_row(const RowView& r, ToWeight<LOGITS> cv, const int* excl,
-                                             int n_excl, const float* slab_w, float u, float& W)
+template <int DT, class CV>
+__device__ __forceinline__ int draw_from_row(const RowView& r, CV cv, const int* excl, int n_excl,
+                                             const float* slab_w, float u, float& W)
 {
     constexpr int E = Elem<DT>::kPerChunk;
     auto sv = [&](int i) { return slab_w[i]; };
     W = slab_total(r.nslab, sv);
     return icdf_slabs<E>(r.nslab, u, W, sv,
-                         [&](int s, float(&w)[E]) { chunk_weights<DT, LOGITS>(r, cv, excl, n_excl, s, w); });
+                         [&](int s, float(&w)[E]) { chunk_weights<DT, CV>(r, cv, excl, n_excl, s, w); });
 }
 
 // ---------------------------------------------------------------- SpecHub element arithmetic
@@ -194,28 +199,31 @@ struct HubScal {
     float iZp, iZq, c;
 };
 
+__device__ __forceinline__ float clamp01(float x) { return __builtin_amdgcn_fmed3f(x, 0.f, 1.f); }
+
+// Every term is a probability (<= 1), so max(x, 0) is written as a clamp to [0, 1], which the
+// hardware applies for free on the instruction that produces x.
 __device__ __forceinline__ void spechub_terms(float ep, float eq, const HubScal& h, float& q_xa_res,
                                               float& q_ax_res, float& w)
 {
     const float Pn = ep * h.iZp;
     const float Qn = eq * h.iZq;
-    const float d = Pn - Qn;
-    q_xa_res = fmaxf(-d, 0.f);
-    const float t = fmaf(h.c, Qn, -fmaxf(d, 0.f));
-    q_ax_res = fmaxf(t, 0.f);
-    w = fmaxf(-t, 0.f);
+    q_xa_res = clamp01(Qn - Pn);                // Q'(y,a) = max(Q - P, 0)
+    const float pr = clamp01(Pn - Qn);          // p'(y)   = max(P - Q, 0)
+    q_ax_res = clamp01(fmaf(h.c, Qn, -pr));     // Q'(a,y) = max(c Q - p', 0)
+    w = clamp01(fmaf(-h.c, Qn, pr));            // p''(y)  = max(p' - c Q, 0)
 }
 
-template <int DT, bool LOGITS>
-__device__ __forceinline__ void spechub_chunk_w(const RowView& rp, const RowView& rq, ToWeight<LOGITS> cp,
-                                                ToWeight<LOGITS> cq, const HubScal& h, int a_virt, int s,
+template <int DT, class CV>
+__device__ __forceinline__ void spechub_chunk_w(const RowView& rp, const RowView& rq, CV cp, CV cq,
+                                                const HubScal& h, int a_virt, int s,
                                                 float (&w)[Elem<DT>::kPerChunk])
 {
     constexpr int E = Elem<DT>::kPerChunk;
     const int chunk = s * 64 + (threadIdx.x & 63);
     float a[E], b[E];
-    load_chunk<DT>(rp, chunk, ToWeight<LOGITS>::fill(), a);
-    load_chunk<DT>(rq, chunk, ToWeight<LOGITS>::fill(), b);
+    load_chunk<DT>(rp, chunk, CV::fill(), a);
+    load_chunk<DT>(rq, chunk, CV::fill(), b);
 #pragma unroll
     for (int e = 0; e < E; ++e) {
         float ep = cp(a[e]), eq = cq(b[e]);
@@ -231,16 +239,16 @@ __device__ __forceinline__ float rrs_term(float ep, float eq, float iZp, float c
     return fmaxf(fmaf(-c_iZq, eq, ep * iZp), 0.f);
 }
 
-template <int DT, bool LOGITS>
-__device__ __forceinline__ void rrs_chunk_w(const RowView& rp, const RowView& rq, ToWeight<LOGITS> cp,
-                                            ToWeight<LOGITS> cq, float iZp, float c_iZq, const int* excl,
-                                            int n_excl, int s, float (&w)[Elem<DT>::kPerChunk])
+template <int DT, class CV>
+__device__ __forceinline__ void rrs_chunk_w(const RowView& rp, const RowView& rq, CV cp, CV cq, float iZp,
+                                            float c_iZq, const int* excl, int n_excl, int s,
+                                            float (&w)[Elem<DT>::kPerChunk])
 {
     constexpr int E = Elem<DT>::kPerChunk;
     const int chunk = s * 64 + (threadIdx.x & 63);
     float a[E], b[E];
-    load_chunk<DT>(rp, chunk, ToWeight<LOGITS>::fill(), a);
-    load_chunk<DT>(rq, chunk, ToWeight<LOGITS>::fill(), b);
+    load_chunk<DT>(rp, chunk, CV::fill(), a);
+    load_chunk<DT>(rq, chunk, CV::fill(), b);
 #pragma unroll
     for (int e = 0; e < E; ++e) w[e] = rrs_term(cp(a[e]), cq(b[e]), iZp, c_iZq);
     zero_excluded<E>(w, chunk, excl, n_excl);
@@ -265,7 +273,324 @@ __device__ __forceinline__ void write_resid_prob(float* out, const RowView& r, f
     }
 }
 
+// ---------------------------------------------------------------- single-read paths (logits in registers)
+struct NodeOut {
+    int outcome, token, flags;
+    float rmass;
+};
+
+using ExpW = ToWeight<true>;  // 2^(l*s - ms)
+
+// Draw from weights held in registers: slab search by every wave, the search inside the slab by
+// the wave that owns it; the result travels through LDS.  weights_of(it, w) gives this lane's
+// weights of its register chunk `it` (run-time value).
+template <int E, class SlabVal, class RegWeights>
+__device__ __forceinline__ int draw_resident(int nslab, float u, float W, SlabVal sv, RegWeights weights_of,
+                                             Shared& sh)
+{
+    SlabHit h;
+    if (!icdf_find_slab(nslab, u, W, sv, h)) return -1;  // same decision in every wave
+    if ((int)(threadIdx.x >> 6) == h.slab % kWaves) {
+        float w[E];
+        weights_of(h.slab / kWaves, w);
+        const int v = icdf_in_slab<E>(w, h);
+        if ((threadIdx.x & 63) == 0) sh.bcast_i = v;
+    }
+    __syncthreads();
+    return sh.bcast_i;
+}
+
+// leaf: bonus token ~ p (the k = 0 case of Alg. 1)
+template <int DT, int NIT, bool MASKED>
+__device__ __forceinline__ void leaf_resident(const Params& P, const RowView& rp,
+                                              const RowSrc<DT, NIT, MASKED>& sp, float u, float* rprob,
+                                              Shared& sh, int& phase, NodeOut& o)
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    float mm[1] = {lane_max(sp)};
+    block_max<kWaves, 1>(mm, sh.red, phase);
+    ExpW cp;
+    cp.s = kLog2e / P.temp_target;
+    cp.ms = mm[0] * cp.s;
+    pass_weights_to_slabs<ExpW>(sp, cp, nullptr, 0, sh.slab_w);
+    __syncthreads();
+    auto sv = [&](int i) { return sh.slab_w[i]; };
+    const float W = slab_total(rp.nslab, sv);
+    const int v = draw_resident<E>(rp.nslab, u, W, sv, [&](int it, float(&w)[E]) {
+        float a[E];
+        get_dyn(sp, it, a);
+#pragma unroll
+        for (int e = 0; e < E; ++e) w[e] = cp(a[e]);
+    }, sh);
+    o.token = v < 0 ? -1 : v - rp.head;
+    if (v < 0) o.flags |= MDSD_FLAG_ZERO_RESIDUAL;
+    o.rmass = 1.f;
+    if (rprob)
+        write_resid_prob<DT>(rprob, rp, W, [&](int s, float(&w)[E]) {
+            chunk_weights<DT, ExpW>(rp, cp, nullptr, 0, s, w);
+        });
+}
+
+// the scalars of one node that come from memory: the pair, the stored logits at its tokens,
+// the uniforms.  Asked for together with the rows, used after the first passes.
+struct NodeIn {
+    int x1, x2;
+    bool tokens_ok;
+    float lp1, lq1, lp2, lq2;
+    float u0, u1, u2;
+};
+
+template <int DT>
+__device__ __forceinline__ void fetch_node_inputs(const Params& P, const NodeId& id, const RowView& rp,
+                                                  const RowView& rq, NodeIn& in)
+{
+    const float* ur = P.u + id.row * 3;
+    in.u0 = ur[0];
+    in.u1 = ur[1];
+    in.u2 = ur[2];
+    in.x1 = in.x2 = -1;
+    in.tokens_ok = false;
+    in.lp1 = in.lq1 = in.lp2 = in.lq2 = 0.f;
+    if (id.c0 >= 0) {
+        const int32_t* xt = P.tokens + (int64_t)id.b * P.N + id.c0;
+        in.x1 = xt[0];
+        in.x2 = xt[1];
+        in.tokens_ok = in.x1 >= 0 && in.x1 < P.V && in.x2 >= 0 && in.x2 < P.V;
+        if (in.tokens_ok) {
+            in.lp1 = load_elem<DT>(rp, in.x1);
+            in.lq1 = load_elem<DT>(rq, in.x1);
+            in.lp2 = load_elem<DT>(rp, in.x2);
+            in.lq2 = load_elem<DT>(rq, in.x2);
+        }
+    }
+}
+
+// internal node, SpecHub (Alg. 3)
+template <int DT, int NIT, bool MASKED>
+__device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& in, const RowView& rp,
+                                                 const RowView& rq, const RowSrc<DT, NIT, MASKED>& sp,
+                                                 const RowSrc<DT, NIT, MASKED>& sq, bool need_full,
+                                                 float* rprob, Shared& sh, int& phase, NodeOut& o)
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int x1 = in.x1, x2 = in.x2;
+    const bool tokens_ok = in.tokens_ok;
+    const float u0 = in.u0, u1 = in.u1, u2 = in.u2;
+
+    // ---- maxima of the stored logits; hub = lowest index among the maxima of the draft row
+    const float mq_lane = lane_max(sq);
+    float mm[2] = {lane_max(sp), mq_lane};
+    block_max<kWaves, 2>(mm, sh.red, phase);
+    int my_idx = INT_MAX;
+    if (mq_lane == mm[1]) my_idx = lane_first_index_of(sq, mm[1]);
+    int a_virt = block_min_index<kWaves>(my_idx, sh.red, phase);
+    const bool owner = my_idx == a_virt && a_virt != INT_MAX;
+    if (a_virt == INT_MAX) a_virt = rq.head;  // a row of NaNs has no maximum: stay in bounds
+    const int a = a_virt - rq.head;
+    if (owner) sh.bcast_f = own_element(sp, a_virt);  // the target's logit at the hub
+    ExpW cp, cq;
+    cp.s = kLog2e / P.temp_target;
+    cp.ms = mm[0] * cp.s;
+    cq.s = kLog2e / P.temp_draft;
+    cq.ms = mm[1] * cq.s;
+
+    // ---- normalisers: Zp and the draft mass outside the hub, Zq' = sum_{y != a} eq (summed
+    // without the hub, never formed as a difference)
+    const int a_slab = a_virt / (64 * E);
+    float z[2] = {0.f, 0.f};
+    for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
+        float wp[E], wq[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            wp[e] = cp(pa_[e]);
+            wq[e] = cq(qa_[e]);
+        }
+        if (s == a_slab) zero_excluded<E>(wq, chunk, &a_virt, 1);
+        z[0] += chunk_sum<E>(wp);
+        z[1] += chunk_sum<E>(wq);
+    });
+    block_sum<kWaves, 2>(z, sh.red, phase);  // barrier: bcast_f visible
+    const float Zq_rest = z[1];
+    const float ea_q = cq(mm[1]);
+    const float ea_p = cp(sh.bcast_f);
+    HubScal h;
+    h.iZp = 1.f / z[0];
+    h.iZq = 1.f / (Zq_rest + ea_q);
+    h.c = ea_q / Zq_rest;  // q(a) / (1 - q(a)); unused when Zq_rest == 0
+    const float pa = ea_p * h.iZp;
+    const float qa = ea_q * h.iZq;
+
+    bool decided = false, degenerate = false;
+    int hub_slot = -1;
+    if (!tokens_ok) {
+        o.flags |= MDSD_FLAG_BAD_TOKEN;
+        o.outcome = MDSD_BAD_TOKEN;
+        decided = true;
+    } else if (!(Zq_rest > 0.f)) {
+        degenerate = true;
+        o.flags |= MDSD_FLAG_DEGENERATE_HUB;
+        if (x1 != a || x2 != a) {
+            o.flags |= MDSD_FLAG_BAD_PAIR;
+            o.outcome = MDSD_BAD_PAIR;
+            decided = true;
+        } else if (u0 * qa < pa) {
+            o.outcome = 0;
+            o.token = a;
+            decided = true;
+        }
+    } else if (x2 == a && x1 != a) {
+        hub_slot = 1;
+        const float px = cp(in.lp1) * h.iZp, qx = cq(in.lq1) * h.iZq;
+        if (u0 * qx < px) {  // pair (x, a): min(p(x)/Q(x,a), 1)
+            o.outcome = 0;
+            o.token = x1;
+            decided = true;
+        }
+    } else if (x1 == a && x2 != a) {
+        hub_slot = 0;
+        const float px = cp(in.lp2) * h.iZp, qx = cq(in.lq2) * h.iZq;
+        if (u0 * (h.c * qx) < fmaxf(px - qx, 0.f)) {  // pair (a, x): min(p'(x)/Q(a,x), 1)
+            o.outcome = 1;
+            o.token = x2;
+            decided = true;
+        }
+    } else {
+        o.flags |= MDSD_FLAG_BAD_PAIR;
+        o.outcome = MDSD_BAD_PAIR;
+        decided = true;
+    }
+    if (decided && !need_full) return;
+
+    if (degenerate) {
+        // residual of the single-draft case: p with the hub removed
+        pass_weights_to_slabs<ExpW>(sp, cp, &a_virt, 1, sh.slab_w);
+        __syncthreads();
+        float W;
+        const int v = draw_from_row<DT, ExpW>(rp, cp, &a_virt, 1, sh.slab_w, u2, W);
+        o.rmass = W * h.iZp;
+        if (!decided) {
+            o.token = v < 0 ? -1 : v - rp.head;
+            if (v < 0) o.flags |= MDSD_FLAG_ZERO_RESIDUAL;
+        }
+        if (rprob)
+            write_resid_prob<DT>(rprob, rp, W, [&](int s, float(&w)[E]) {
+                chunk_weights<DT, ExpW>(rp, cp, &a_virt, 1, s, w);
+            });
+        return;
+    }
+
+    // ---- residual sums: S_xa = sum Q'(.,a), S_ax = sum Q'(a,.), slab sums of p''
+    float sacc[2] = {0.f, 0.f};
+    for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
+        float ep[E], eq[E], t_xa[E], t_ax[E], w[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            ep[e] = cp(pa_[e]);
+            eq[e] = cq(qa_[e]);
+        }
+        if (s == a_slab) {
+            zero_excluded<E>(ep, chunk, &a_virt, 1);
+            zero_excluded<E>(eq, chunk, &a_virt, 1);
+        }
+#pragma unroll
+        for (int e = 0; e < E; ++e) spechub_terms(ep[e], eq[e], h, t_xa[e], t_ax[e], w[e]);
+        sacc[0] += chunk_sum<E>(t_xa);
+        sacc[1] += chunk_sum<E>(t_ax);
+        store_slab_sum(sh.slab_w, s, chunk_sum<E>(w));
+    });
+    block_sum<kWaves, 2>(sacc, sh.red, phase);  // barrier: slab sums visible
+    const float S_xa = sacc[0], S_ax = sacc[1];
+    if (!decided) {
+        if (hub_slot == 1) {  // pair (x, a): the hub draws on what the pairs (a,.) left of p(a)
+            if (u1 * S_xa < fmaxf(pa - S_ax, 0.f)) {
+                o.outcome = 1;
+                o.token = a;
+                decided = true;
+            }
+        } else if (u1 * S_ax < pa) {  // pair (a, x)
+            o.outcome = 0;
+            o.token = a;
+            decided = true;
+        }
+    }
+    auto sv = [&](int i) { return sh.slab_w[i]; };
+    const float W = slab_total(rp.nslab, sv);
+    o.rmass = W;
+    bool wrote_prob = false;
+    if (!decided) {
+        int v = draw_resident<E>(rp.nslab, u2, W, sv, [&](int it, float(&w)[E]) {
+            float a_[E], b_[E];
+            get_dyn(sp, it, a_);
+            get_dyn(sq, it, b_);
+            const int chunk = (it * kWaves + wave) * 64 + lane;
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                float ep = cp(a_[e]), eq = cq(b_[e]);
+                if (chunk * E + e == a_virt) ep = eq = 0.f;
+                float t0, t1;
+                spechub_terms(ep, eq, h, t0, t1, w[e]);
+            }
+        }, sh);
+        if (v < 0) {
+            // no residual mass: fall back to p itself
+            o.flags |= MDSD_FLAG_ZERO_RESIDUAL;
+            __syncthreads();
+            pass_weights_to_slabs<ExpW>(sp, cp, nullptr, 0, sh.slab_w);
+            __syncthreads();
+            float Wp;
+            v = draw_from_row<DT, ExpW>(rp, cp, nullptr, 0, sh.slab_w, u2, Wp);
+            if (rprob) {
+                write_resid_prob<DT>(rprob, rp, Wp, [&](int s, float(&w)[E]) {
+                    chunk_weights<DT, ExpW>(rp, cp, nullptr, 0, s, w);
+                });
+                wrote_prob = true;
+            }
+        }
+        o.token = v < 0 ? -1 : v - rp.head;
+    }
+    if (rprob && !wrote_prob)
+        write_resid_prob<DT>(rprob, rp, W, [&](int s, float(&w)[E]) {
+            spechub_chunk_w<DT, ExpW>(rp, rq, cp, cq, h, a_virt, s, w);
+        });
+}
+
+// SpecHub verify for logit rows that fit in registers: one workgroup per node, every load of the
+// node queued before anything waits, all passes from registers.
+template <int DT, int NIT, bool MASKED>
+__global__ __launch_bounds__(kWG, (NIT <= 8 ? 4 : 2)) void spechub_verify_resident(const Params P)
+{
+    __shared__ Shared sh;
+    int phase = 0;
+    const NodeId id = node_of_block(P);
+    const bool need_full = (P.resid_mass != nullptr) || (P.resid_prob != nullptr);
+    float* rprob = P.resid_prob ? P.resid_prob + id.row * (int64_t)P.V : nullptr;
+    const RowView rp = make_row<DT>(P.target, P.ld_t, id.row, P.V);
+    RowView rq = rp;
+    RowSrc<DT, NIT, MASKED> sp, sq;
+    sp.issue(rp, ExpW::fill());
+    if (id.c0 >= 0) {
+        rq = make_row<DT>(P.draft, P.ld_d, id.row, P.V);
+        sq.issue(rq, ExpW::fill());
+    }
+    NodeIn in;
+    fetch_node_inputs<DT>(P, id, rp, rq, in);
+    NodeOut o{MDSD_NONE, -1, 0, 0.f};
+    if (id.c0 < 0)
+        leaf_resident<DT, NIT, MASKED>(P, rp, sp, in.u2, rprob, sh, phase, o);
+    else
+        spechub_resident<DT, NIT, MASKED>(P, in, rp, rq, sp, sq, need_full, rprob, sh, phase, o);
+    if (threadIdx.x == 0) {
+        P.outcome[id.row] = o.outcome;
+        P.token[id.row] = o.token;
+        if (P.resid_mass) P.resid_mass[id.row] = o.rmass;
+        if (P.flags) P.flags[id.row] = o.flags;
+    }
+}
+
 // ---------------------------------------------------------------- verify kernel
+// Two workgroups per CU need 4 waves per SIMD, i.e. at most 128 VGPRs; the 16-chunk variant
+// holds 128 VGPRs of row data alone and runs one workgroup per CU.
 template <int DT, bool LOGITS, int METHOD, int NIT>
 __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
 {
@@ -282,9 +607,10 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
 
     const RowView rp = make_row<DT>(P.target, P.ld_t, id.row, P.V);
     Src sp;
-    sp.init(rp, CV::fill());
     int outcome = MDSD_NONE, token = -1, flags = 0;
     float rmass = 0.f;
+
+    sp.init(rp, CV::fill());
 
     if (id.c0 < 0) {
         // ---- leaf: the k = 0 case of Alg. 1, token ~ p
@@ -295,16 +621,16 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
             cp.s = kLog2e / P.temp_target;
             cp.ms = mm[0] * cp.s;
         }
-        pass_weights_to_slabs<LOGITS>(sp, cp, nullptr, 0, sh.slab_w);
+        pass_weights_to_slabs<CV>(sp, cp, nullptr, 0, sh.slab_w);
         __syncthreads();
         float W;
-        const int v = draw_from_row<DT, LOGITS>(rp, cp, nullptr, 0, sh.slab_w, ur[k], W);
+        const int v = draw_from_row<DT, CV>(rp, cp, nullptr, 0, sh.slab_w, ur[k], W);
         token = v < 0 ? -1 : v - rp.head;
         if (v < 0) flags |= MDSD_FLAG_ZERO_RESIDUAL;
         rmass = LOGITS ? 1.f : W;
         if (rprob)
             write_resid_prob<DT>(rprob, rp, W, [&](int s, float(&w)[E]) {
-                chunk_weights<DT, LOGITS>(rp, cp, nullptr, 0, s, w);
+                chunk_weights<DT, CV>(rp, cp, nullptr, 0, s, w);
             });
     } else {
         const RowView rq = make_row<DT>(P.draft, P.ld_d, id.row, P.V);
@@ -329,7 +655,7 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
             // ---- normalisers: Zp (logits only) and D-part Zq' = sum_{y != a} eq
             const int a_slab = a_virt / (64 * E);
             float z[2] = {0.f, 0.f};
-            for_each2<DT, NIT>(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
+            for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
                 float wp[E], wq[E];
 #pragma unroll
                 for (int e = 0; e < E; ++e) {
@@ -397,10 +723,10 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
             if (!decided || need_full) {
                 if (degenerate) {
                     // residual of the single-draft case: p with the hub removed
-                    pass_weights_to_slabs<LOGITS>(sp, cp, &a_virt, 1, sh.slab_w);
+                    pass_weights_to_slabs<CV>(sp, cp, &a_virt, 1, sh.slab_w);
                     __syncthreads();
                     float W;
-                    const int v = draw_from_row<DT, LOGITS>(rp, cp, &a_virt, 1, sh.slab_w, ur[2], W);
+                    const int v = draw_from_row<DT, CV>(rp, cp, &a_virt, 1, sh.slab_w, ur[2], W);
                     rmass = W * h.iZp;
                     if (!decided) {
                         token = v < 0 ? -1 : v - rp.head;
@@ -408,12 +734,12 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
                     }
                     if (rprob)
                         write_resid_prob<DT>(rprob, rp, W, [&](int s, float(&w)[E]) {
-                            chunk_weights<DT, LOGITS>(rp, cp, &a_virt, 1, s, w);
+                            chunk_weights<DT, CV>(rp, cp, &a_virt, 1, s, w);
                         });
                 } else {
                     // ---- residual sums: S_xa = sum Q'(.,a), S_ax = sum Q'(a,.), slab sums of p''
                     float sacc[2] = {0.f, 0.f};
-                    for_each2<DT, NIT>(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
+                    for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
                         float ep[E], eq[E], t_xa[E], t_ax[E], w[E];
 #pragma unroll
                         for (int e = 0; e < E; ++e) {
@@ -450,7 +776,7 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
                     }
                     auto sv = [&](int i) { return sh.slab_w[i]; };
                     auto cw = [&](int s, float(&w)[E]) {
-                        spechub_chunk_w<DT, LOGITS>(rp, rq, cp, cq, h, a_virt, s, w);
+                        spechub_chunk_w<DT, CV>(rp, rq, cp, cq, h, a_virt, s, w);
                     };
                     const float W = slab_total(rp.nslab, sv);
                     rmass = W;
@@ -461,13 +787,13 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
                             // no residual mass: fall back to p itself
                             flags |= MDSD_FLAG_ZERO_RESIDUAL;
                             __syncthreads();
-                            pass_weights_to_slabs<LOGITS>(sp, cp, nullptr, 0, sh.slab_w);
+                            pass_weights_to_slabs<CV>(sp, cp, nullptr, 0, sh.slab_w);
                             __syncthreads();
                             float Wp;
-                            v = draw_from_row<DT, LOGITS>(rp, cp, nullptr, 0, sh.slab_w, ur[2], Wp);
+                            v = draw_from_row<DT, CV>(rp, cp, nullptr, 0, sh.slab_w, ur[2], Wp);
                             if (rprob) {
                                 write_resid_prob<DT>(rprob, rp, Wp, [&](int s, float(&w)[E]) {
-                                    chunk_weights<DT, LOGITS>(rp, cp, nullptr, 0, s, w);
+                                    chunk_weights<DT, CV>(rp, cp, nullptr, 0, s, w);
                                 });
                                 wrote_prob = true;
                             }
@@ -509,7 +835,7 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
                 // normalisers; without replacement the draft sum leaves out every draft token,
                 // so that the mass remaining after i removals is a sum of positive terms
                 float z[2] = {0.f, 0.f};
-                for_each2<DT, NIT>(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
+                for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
                     float wp[E], wq[E];
 #pragma unroll
                     for (int e = 0; e < E; ++e) {
@@ -561,7 +887,7 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
                     n_rej = i + 1;
                     if (i > 0) __syncthreads();  // earlier readers of slab_w are done
                     const float c_iZq = c_new * iZq;
-                    for_each2<DT, NIT>(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
+                    for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
                         float w[E];
 #pragma unroll
                         for (int e = 0; e < E; ++e) w[e] = rrs_term(cp(pa_[e]), cq(qa_[e]), iZp, c_iZq);
@@ -589,13 +915,13 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
                 if (!decided || need_full) {
                     const float c_iZq = c * iZq;
                     auto cw = [&](int s, float(&w)[E]) {
-                        rrs_chunk_w<DT, LOGITS>(rp, rq, cp, cq, iZp, c_iZq, xv, n_rej, s, w);
+                        rrs_chunk_w<DT, CV>(rp, rq, cp, cq, iZp, c_iZq, xv, n_rej, s, w);
                     };
                     if (slab_c != c || slab_nx != n_rej) {
                         // the slab sums in LDS are not those of the current residual (accepted in
                         // the first round, or a round without mass): rebuild them
                         __syncthreads();
-                        for_each2<DT, NIT>(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
+                        for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
                             float w[E];
 #pragma unroll
                             for (int e = 0; e < E; ++e) w[e] = rrs_term(cp(pa_[e]), cq(qa_[e]), iZp, c_iZq);
@@ -666,7 +992,7 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
             cq.ms = mm[0] * cq.s;
         }
     }
-    pass_weights_to_slabs<LOGITS>(sq, cq, nullptr, 0, sh.slab_w);
+    pass_weights_to_slabs<CV>(sq, cq, nullptr, 0, sh.slab_w);
     __syncthreads();
 
     // slab sums with some tokens removed: only the slabs holding a removed token change,
@@ -681,7 +1007,7 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
             if (ov_slab[j] == i) v = ov_val[j];
         return v;
     };
-    auto cw = [&](int s, float(&w)[E]) { chunk_weights<DT, LOGITS>(rq, cq, excl, n_excl, s, w); };
+    auto cw = [&](int s, float(&w)[E]) { chunk_weights<DT, CV>(rq, cq, excl, n_excl, s, w); };
     auto remove_token = [&](int v) {
         excl[n_excl++] = v;
         const int s = v / (64 * E);
@@ -884,12 +1210,47 @@ static void launch_verify_n(int nit, dim3 grid, dim3 block, hipStream_t st, cons
     }
 }
 
+template <int DT>
+static void launch_spechub_resident(int nit, bool masked, dim3 grid, dim3 block, hipStream_t st, const Params& P)
+{
+#define MDSD_LAUNCH_RES(N)                                                                          \
+    if (masked)                                                                                     \
+        hipLaunchKernelGGL((spechub_verify_resident<DT, N, true>), grid, block, 0, st, P);          \
+    else                                                                                            \
+        hipLaunchKernelGGL((spechub_verify_resident<DT, N, false>), grid, block, 0, st, P)
+    if (nit == 4) {
+        MDSD_LAUNCH_RES(4);
+    } else if (nit == 8) {
+        MDSD_LAUNCH_RES(8);
+    } else {
+        MDSD_LAUNCH_RES(16);
+    }
+#undef MDSD_LAUNCH_RES
+}
+
+// true when some element of some row may need masking: a row that does not start on a
+// 16-byte boundary, or a vocabulary that is not a whole number of 16-byte chunks
+static bool rows_need_mask(const mdsd_problem* pb)
+{
+    const int es = pb->dtype == MDSD_FP32 ? 4 : 2;
+    const uintptr_t at = (uintptr_t)pb->target, ad = (uintptr_t)pb->draft;
+    return (at & 15) || (ad & 15) || ((pb->ld_t * es) & 15) || ((pb->ld_d * es) & 15) || (pb->V % (16 / es));
+}
+
 template <int METHOD>
 static void launch_verify(const mdsd_problem* pb, const Params& P, hipStream_t st)
 {
     const dim3 grid((unsigned)(P.B * P.N)), block(kWG);
     const bool lg = pb->kind == MDSD_LOGITS;
-    const int nit = resident_chunks(pb);
+    int nit = resident_chunks(pb);
+    if (METHOD == kSpecHub && lg && nit > 0) {
+        if (pb->dtype == MDSD_FP32)
+            launch_spechub_resident<0>(nit, rows_need_mask(pb), grid, block, st, P);
+        else
+            launch_spechub_resident<1>(nit, rows_need_mask(pb), grid, block, st, P);
+        return;
+    }
+    if (METHOD != kSpecHub && nit == 16) nit = 0;  // the RRS rounds would spill with 128 registers of row data
     if (pb->dtype == MDSD_FP32) {
         if (lg)
             launch_verify_n<0, true, METHOD>(nit, grid, block, st, P);

@@ -20,8 +20,22 @@ template <> struct Elem<1> {  // bf16
     static constexpr int kPerChunk = 8;
 };
 
+// Row pointers are rebuilt from integer addresses, which would leave the compiler with generic
+// ("flat") pointers; flat loads also count against the LDS counter, so every wait on an LDS
+// operation would wait for the rows as well.  Naming the global address space keeps the row
+// loads on the vector-memory counter alone.
+#define MDSD_GLOBAL __attribute__((address_space(1)))
+typedef uint32_t v4u32 __attribute__((ext_vector_type(4)));
+typedef const MDSD_GLOBAL v4u32* GlobalChunks;
+
+__device__ __forceinline__ uint4 load16(GlobalChunks p, int i)
+{
+    const v4u32 v = p[i];
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 struct RowView {
-    const uint4* chunks;  // 16-byte aligned
+    GlobalChunks chunks;  // 16-byte aligned
     int head;             // masked elements in front of token 0
     int nvirt;            // head + V
     int nchunk;           // chunks that hold at least one real element
@@ -35,7 +49,7 @@ __device__ __forceinline__ RowView make_row(const void* base, int64_t ld, int64_
                            static_cast<uintptr_t>(row * ld) * Elem<DT>::kBytes;
     const int mis = static_cast<int>(addr & 15);
     RowView r;
-    r.chunks = reinterpret_cast<const uint4*>(addr - mis);
+    r.chunks = reinterpret_cast<GlobalChunks>(addr - mis);
     r.head = mis / Elem<DT>::kBytes;
     r.nvirt = r.head + V;
     r.nchunk = (r.nvirt + Elem<DT>::kPerChunk - 1) / Elem<DT>::kPerChunk;
@@ -49,9 +63,9 @@ __device__ __forceinline__ float load_elem(const RowView& r, int x)
 {
     const int v = r.head + x;
     if constexpr (DT == 0) {
-        return reinterpret_cast<const float*>(r.chunks)[v];
+        return reinterpret_cast<const MDSD_GLOBAL float*>(r.chunks)[v];
     } else {
-        const uint32_t h = reinterpret_cast<const uint16_t*>(r.chunks)[v];
+        const uint32_t h = reinterpret_cast<const MDSD_GLOBAL uint16_t*>(r.chunks)[v];
         return __builtin_bit_cast(float, h << 16);
     }
 }
@@ -82,7 +96,7 @@ __device__ __forceinline__ void load_chunk(const RowView& r, int chunk, float fi
 {
     constexpr int E = Elem<DT>::kPerChunk;
     if (chunk < r.nchunk) {
-        const uint4 d = r.chunks[chunk];
+        const uint4 d = load16(r.chunks, chunk);
         unpack<DT>(d, v);
         const int v0 = chunk * E;
         if (v0 < r.head || v0 + E > r.nvirt) {

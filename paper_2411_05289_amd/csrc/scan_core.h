@@ -57,42 +57,49 @@ __device__ __forceinline__ float chunk_sum(const float (&w)[E])
 // registers for all passes (V up to NIT * kWaves * 64 chunks); chunk `it` of a
 // lane belongs to slab it * kWaves + wave, so each load instruction of a wave
 // still covers 1 KiB of consecutive memory.  Masked elements hold `fill`.
-template <int DT, int NIT>
+// MASKED = false: the caller has checked that every row starts on a 16-byte boundary and
+// that V is a whole number of chunks, so no element ever needs masking.
+template <int DT, int NIT, bool MASKED = true>
 struct RowSrc {
     static constexpr int E = Elem<DT>::kPerChunk;
     RowView r;
+    float fill;
     uint4 d[NIT];
 
-    __device__ __forceinline__ void init(const RowView& rv, float fill)
+    // queue the loads of the whole row; nothing waits here
+    __device__ __forceinline__ void issue(const RowView& rv, float f)
     {
         r = rv;
+        fill = f;
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-        const uint32_t fb = __builtin_bit_cast(uint32_t, fill);
+        const uint32_t fb = __builtin_bit_cast(uint32_t, f);
         const uint32_t fw = DT == 0 ? fb : ((fb >> 16) | (fb & 0xffff0000u));
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             const int chunk = (it * kWaves + wave) * 64 + lane;
-            d[it] = chunk < r.nchunk ? r.chunks[chunk] : make_uint4(fw, fw, fw, fw);
+            d[it] = chunk < r.nchunk ? load16(r.chunks, chunk) : make_uint4(fw, fw, fw, fw);
         }
-        // the first and the last chunk of the row may hold elements that are not the row's
+    }
+    __device__ __forceinline__ void init(const RowView& rv, float f) { issue(rv, f); }
+
+    // the first and the last chunk of the row may hold elements that are not the row's:
+    // those read as `fill`.  The registers themselves are left alone.
+    __device__ __forceinline__ void mask(int chunk, float (&a)[E]) const
+    {
+        if constexpr (!MASKED) return;
+        const int v0 = chunk * E;
+        if (v0 < r.head || v0 + E > r.nvirt) {
 #pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            const int chunk = (it * kWaves + wave) * 64 + lane;
-            const int v0 = chunk * E;
-            if (chunk < r.nchunk && (v0 < r.head || v0 + E > r.nvirt)) {
-                float v[E];
-                unpack<DT>(d[it], v);
-                uint32_t w[E];
-#pragma unroll
-                for (int e = 0; e < E; ++e)
-                    w[e] = (v0 + e < r.head || v0 + e >= r.nvirt) ? fb : __builtin_bit_cast(uint32_t, v[e]);
-                if constexpr (DT == 0)
-                    d[it] = make_uint4(w[0], w[1], w[2], w[3]);
-                else
-                    d[it] = make_uint4((w[0] >> 16) | (w[1] & 0xffff0000u), (w[2] >> 16) | (w[3] & 0xffff0000u),
-                                       (w[4] >> 16) | (w[5] & 0xffff0000u), (w[6] >> 16) | (w[7] & 0xffff0000u));
-            }
+            for (int e = 0; e < E; ++e)
+                if (v0 + e < r.head || v0 + e >= r.nvirt) a[e] = fill;
         }
+    }
+
+    // this lane's register chunk `it` as floats (it: compile-time constant after unrolling)
+    __device__ __forceinline__ void get(int it, float (&a)[E]) const
+    {
+        unpack<DT>(d[it], a);
+        mask((it * kWaves + (int)(threadIdx.x >> 6)) * 64 + (int)(threadIdx.x & 63), a);
     }
 
     // body(slab, chunk, a[E])
@@ -105,15 +112,15 @@ struct RowSrc {
             const int s = it * kWaves + wave;
             if (s < r.nslab) {
                 float a[E];
-                unpack<DT>(d[it], a);
+                get(it, a);
                 body(s, s * 64 + lane, a);
             }
         }
     }
 };
 
-template <int DT>
-struct RowSrc<DT, 0> {
+template <int DT, bool MASKED>
+struct RowSrc<DT, 0, MASKED> {
     static constexpr int E = Elem<DT>::kPerChunk;
     RowView r;
     float fill;
@@ -123,6 +130,7 @@ struct RowSrc<DT, 0> {
         r = rv;
         fill = f;
     }
+    __device__ __forceinline__ void issue(const RowView& rv, float f) { init(rv, f); }
 
     template <class Body>
     __device__ __forceinline__ void for_each(Body body) const
@@ -137,8 +145,9 @@ struct RowSrc<DT, 0> {
 };
 
 // body(slab, chunk, a[E], b[E]) over two rows with the same head and length
-template <int DT, int NIT, class Body>
-__device__ __forceinline__ void for_each2(const RowSrc<DT, NIT>& sa, const RowSrc<DT, NIT>& sb, Body body)
+template <int DT, int NIT, bool MASKED, class Body>
+__device__ __forceinline__ void for_each2(const RowSrc<DT, NIT, MASKED>& sa, const RowSrc<DT, NIT, MASKED>& sb,
+                                          Body body)
 {
     constexpr int E = Elem<DT>::kPerChunk;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -155,10 +164,11 @@ __device__ __forceinline__ void for_each2(const RowSrc<DT, NIT>& sa, const RowSr
             const int s = it * kWaves + wave;
             if (s < sa.r.nslab) {
                 float a[E], b[E];
-                unpack<DT>(sa.d[it], a);
-                unpack<DT>(sb.d[it], b);
+                sa.get(it, a);
+                sb.get(it, b);
                 body(s, s * 64 + lane, a, b);
             }
+            __builtin_amdgcn_sched_barrier(0);  // one chunk pair at a time
         }
     }
 }
@@ -184,46 +194,60 @@ __device__ __forceinline__ float slab_total(int nslab, SlabVal slab_val)
     return W;
 }
 
-// Inverse CDF: virtual index of the first element whose running sum exceeds
-// u * W, where W = slab_total.  slab_val(i) gives the sum of slab i;
-// weights(s, w) recomputes this lane's chunk of slab s.  Returns -1 when
-// W == 0.  If rounding leaves no crossing, the last element with positive
-// weight is returned.  Every wave runs the search redundantly.
-template <int E, class SlabVal, class Weights>
-__device__ __forceinline__ int icdf_slabs(int nslab, float u, float W, SlabVal slab_val,
-                                          Weights weights)
+// Inverse CDF in two stages.  Stage 1 (every wave, redundantly): scan the slab
+// sums for the first slab whose running sum exceeds t = u * W.  Returns false
+// when there is nothing to draw (W == 0).  If rounding leaves no crossing the
+// last slab with positive sum is taken and t becomes +inf, so that stage 2
+// falls through to its last positive element.
+struct SlabHit {
+    int slab;    // slab that holds the drawn element
+    float excl;  // running sum in front of that slab
+    float t;     // threshold
+};
+
+template <class SlabVal>
+__device__ __forceinline__ bool icdf_find_slab(int nslab, float u, float W, SlabVal slab_val, SlabHit& h)
 {
     const int lane = threadIdx.x & 63;
-    if (!(W > 0.f)) return -1;
-    float t = u * W;
-    float carry = 0.f, excl_hit = 0.f;
-    int s_hit = -1, last_pos = -1;
+    if (!(W > 0.f)) return false;
+    h.t = u * W;
+    h.excl = 0.f;
+    h.slab = -1;
+    float carry = 0.f;
+    int last_pos = -1;
     for (int base = 0; base < nslab; base += 64) {
         const float v = (base + lane < nslab) ? slab_val(base + lane) : 0.f;
         const float incl = wave_scan_add(v);
         const float excl = carry + wave_shift_up(incl, 0.f);
-        const unsigned long long hit = __ballot(carry + incl > t);
+        const unsigned long long hit = __ballot(carry + incl > h.t);
         const unsigned long long pos = __ballot(v > 0.f);
         if (hit) {
             const int l = __ffsll(hit) - 1;
-            s_hit = base + l;
-            excl_hit = __shfl(excl, l, 64);
-            break;
+            h.slab = base + l;
+            h.excl = __shfl(excl, l, 64);
+            return true;
         }
         if (pos) last_pos = base + 63 - __clzll(pos);
         carry += lane_bcast(incl, 63);
     }
-    if (s_hit < 0) {  // t >= W after rounding: take the last positive element
-        if (last_pos < 0) return -1;
-        s_hit = last_pos;
-        t = __builtin_inff();
-    }
-    float w[E];
-    weights(s_hit, w);
+    if (last_pos < 0) return false;
+    h.slab = last_pos;
+    h.t = __builtin_inff();
+    return true;
+}
+
+// Stage 2 (one wave): w = this lane's chunk of the slab found in stage 1.
+// Returns the virtual index of the first element whose running sum exceeds t,
+// else the last element with positive weight, else -1 (same value in every lane).
+template <int E>
+__device__ __forceinline__ int icdf_in_slab(const float (&w)[E], const SlabHit& h)
+{
+    const int lane = threadIdx.x & 63;
+    float t = h.t;
     const float ls = chunk_sum<E>(w);
     const float incl = wave_scan_add(ls);
     const float lane_excl = wave_shift_up(incl, 0.f);
-    const unsigned long long hit = __ballot(excl_hit + incl > t);
+    const unsigned long long hit = __ballot(h.excl + incl > t);
     const unsigned long long pos = __ballot(ls > 0.f);
     int l;
     if (hit) {
@@ -233,7 +257,7 @@ __device__ __forceinline__ int icdf_slabs(int nslab, float u, float W, SlabVal s
         l = 63 - __clzll(pos);
         t = __builtin_inff();
     }
-    float run = excl_hit + lane_excl;
+    float run = h.excl + lane_excl;
     int e_sel = -1, e_last = -1;
 #pragma unroll
     for (int e = 0; e < E; ++e) {
@@ -242,8 +266,19 @@ __device__ __forceinline__ int icdf_slabs(int nslab, float u, float W, SlabVal s
         if (e_sel < 0 && run > t) e_sel = e;
     }
     if (e_sel < 0) e_sel = e_last;
-    const int vidx = (e_sel < 0) ? -1 : (s_hit * 64 + lane) * E + e_sel;
+    const int vidx = (e_sel < 0) ? -1 : (h.slab * 64 + lane) * E + e_sel;
     return __shfl(vidx, l, 64);
+}
+
+// Both stages with the chunk recomputed by weights(s, w); every wave runs it redundantly.
+template <int E, class SlabVal, class Weights>
+__device__ __forceinline__ int icdf_slabs(int nslab, float u, float W, SlabVal slab_val, Weights weights)
+{
+    SlabHit h;
+    if (!icdf_find_slab(nslab, u, W, slab_val, h)) return -1;
+    float w[E];
+    weights(h.slab, w);
+    return icdf_in_slab<E>(w, h);
 }
 
 }  // namespace mdsd
