@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--copies", type=int, default=0, help="distinct input copies to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain 512 MiB device copy three times (reference dispatch for "
+                         "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
 
 
@@ -113,6 +116,13 @@ def main():
         pl.walk(stream)
         return pl.out["accept_depth"]
 
+    if args.calibration_copy:
+        src = torch.empty(512 * 2 ** 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -151,7 +161,7 @@ def main():
         sample_B = min(Bn, max(1, (64 * 32000) // wl0.V))     # about 2000 config-3-sized node rows
         rows = (W.rows_as_numpy(wl0.target[:sample_B]), W.rows_as_numpy(wl0.draft[:sample_B]))
         method_id = {"spechub": 0, "rrs": 1, "rrsw": 2}[args.method]
-        repeats = 8
+        repeats = 24
         v, secs = cpu_baseline(rows, k, wl0.depth, (wl0.temp_target, wl0.temp_draft), method_id, repeats, threads)
         out["cpu_baseline"] = {"value": v, "unit": "nodes/s", "cores": threads, "kind": "oracle",
                                "sample": "%d trees (%d nodes) of the same batch x %d repeats, %.1f s wall"
