@@ -131,11 +131,8 @@ __device__ __forceinline__ void zero_excluded(float (&w)[E], int chunk, const in
 {
     for (int j = 0; j < n_excl; ++j) {
         const int off = excl[j] - chunk * E;
-        if (off >= 0 && off < E) {
 #pragma unroll
-            for (int e = 0; e < E; ++e)
-                if (e == off) w[e] = 0.f;
-        }
+        for (int e = 0; e < E; ++e) w[e] = (e == off) ? 0.f : w[e];
     }
 }
 
@@ -259,7 +256,7 @@ template <int DT, class ChunkW>
 __device__ __forceinline__ void write_resid_prob(float* out, const RowView& r, float W, ChunkW cw)
 {
     constexpr int E = Elem<DT>::kPerChunk;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = wave_id();
     const float iW = W > 0.f ? 1.f / W : 0.f;
     for (int s = wave; s < r.nslab; s += kWaves) {
         float w[E];
@@ -290,7 +287,7 @@ __device__ __forceinline__ int draw_resident(int nslab, float u, float W, SlabVa
 {
     SlabHit h;
     if (!icdf_find_slab(nslab, u, W, sv, h)) return -1;  // same decision in every wave
-    if ((int)(threadIdx.x >> 6) == h.slab % kWaves) {
+    if (wave_id() == h.slab % kWaves) {
         float w[E];
         weights_of(h.slab / kWaves, w);
         const int v = icdf_in_slab<E>(w, h);
@@ -373,7 +370,7 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
                                                  float* rprob, Shared& sh, int& phase, NodeOut& o)
 {
     constexpr int E = Elem<DT>::kPerChunk;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = wave_id();
     const int x1 = in.x1, x2 = in.x2;
     const bool tokens_ok = in.tokens_ok;
     const float u0 = in.u0, u1 = in.u1, u2 = in.u2;
@@ -387,6 +384,7 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
     int a_virt = block_min_index<kWaves>(my_idx, sh.red, phase);
     const bool owner = my_idx == a_virt && a_virt != INT_MAX;
     if (a_virt == INT_MAX) a_virt = rq.head;  // a row of NaNs has no maximum: stay in bounds
+    a_virt = __builtin_amdgcn_readfirstlane(a_virt);
     const int a = a_virt - rq.head;
     if (owner) sh.bcast_f = own_element(sp, a_virt);  // the target's logit at the hub
     ExpW cp, cq;

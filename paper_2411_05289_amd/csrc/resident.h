@@ -30,7 +30,7 @@ template <int DT, int NIT, bool MASKED>
 __device__ __forceinline__ void get_dyn(const RowSrc<DT, NIT, MASKED>& src, int it, float (&a)[Elem<DT>::kPerChunk])
 {
     unpack<DT>(select_chunk<NIT>(src.d, it), a);
-    src.mask((it * kWaves + (int)(threadIdx.x >> 6)) * 64 + (int)(threadIdx.x & 63), a);
+    src.mask((it * kWaves + wave_id()) * 64 + (int)(threadIdx.x & 63), a);
 }
 
 // the element of this lane's registers at virtual index v (the lane must own v)

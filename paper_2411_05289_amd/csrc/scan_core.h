@@ -71,7 +71,7 @@ struct RowSrc {
     {
         r = rv;
         fill = f;
-        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const int lane = threadIdx.x & 63, wave = wave_id();
         const uint32_t fb = __builtin_bit_cast(uint32_t, f);
         const uint32_t fw = DT == 0 ? fb : ((fb >> 16) | (fb & 0xffff0000u));
 #pragma unroll
@@ -99,14 +99,14 @@ struct RowSrc {
     __device__ __forceinline__ void get(int it, float (&a)[E]) const
     {
         unpack<DT>(d[it], a);
-        mask((it * kWaves + (int)(threadIdx.x >> 6)) * 64 + (int)(threadIdx.x & 63), a);
+        mask((it * kWaves + wave_id()) * 64 + (int)(threadIdx.x & 63), a);
     }
 
     // body(slab, chunk, a[E])
     template <class Body>
     __device__ __forceinline__ void for_each(Body body) const
     {
-        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const int lane = threadIdx.x & 63, wave = wave_id();
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             const int s = it * kWaves + wave;
@@ -135,7 +135,7 @@ struct RowSrc<DT, 0, MASKED> {
     template <class Body>
     __device__ __forceinline__ void for_each(Body body) const
     {
-        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const int lane = threadIdx.x & 63, wave = wave_id();
         for (int s = wave; s < r.nslab; s += kWaves) {
             float a[E];
             load_chunk<DT>(r, s * 64 + lane, fill, a);
@@ -150,7 +150,7 @@ __device__ __forceinline__ void for_each2(const RowSrc<DT, NIT, MASKED>& sa, con
                                           Body body)
 {
     constexpr int E = Elem<DT>::kPerChunk;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = wave_id();
     if constexpr (NIT == 0) {
         for (int s = wave; s < sa.r.nslab; s += kWaves) {
             float a[E], b[E];

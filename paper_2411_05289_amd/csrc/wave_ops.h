@@ -9,6 +9,14 @@ namespace mdsd {
 
 constexpr int kWave = 64;
 
+// index of this wavefront in its workgroup, as a scalar: the compiler cannot see that
+// threadIdx.x / 64 is the same in all 64 lanes, and would otherwise guard every per-wave
+// decision with an execution mask instead of a scalar branch
+__device__ __forceinline__ int wave_id()
+{
+    return __builtin_amdgcn_readfirstlane((int)(threadIdx.x / 64u));
+}
+
 __device__ __forceinline__ float as_f(int v) { return __builtin_bit_cast(float, v); }
 __device__ __forceinline__ int as_i(float v) { return __builtin_bit_cast(int, v); }
 
@@ -72,7 +80,7 @@ template <int WAVES, int NV>
 __device__ __forceinline__ void block_sum(float (&v)[NV], BlockScratch<WAVES>& s, int& phase)
 {
     static_assert(NV <= 4, "at most four values per reduction");
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = wave_id();
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         float t = wave_scan_add(v[i]);
@@ -93,7 +101,7 @@ template <int WAVES, int NV>
 __device__ __forceinline__ void block_max(float (&v)[NV], BlockScratch<WAVES>& s, int& phase)
 {
     static_assert(NV <= 4, "at most four values per reduction");
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = wave_id();
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         float t = wave_scan_max(v[i]);
@@ -114,7 +122,7 @@ __device__ __forceinline__ void block_max(float (&v)[NV], BlockScratch<WAVES>& s
 template <int WAVES>
 __device__ __forceinline__ int block_min_index(int idx, BlockScratch<WAVES>& s, int& phase)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = wave_id();
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) idx = min(idx, __shfl_xor(idx, off, 64));
     if (lane == 0) s.ibuf[phase][wave] = idx;
