@@ -404,7 +404,10 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
             wp[e] = cp(pa_[e]);
             wq[e] = cq(qa_[e]);
         }
-        if (s == a_slab) zero_excluded<E>(wq, chunk, &a_virt, 1);
+        if (__builtin_expect(s == a_slab, 0)) {  // one slab of the row: a real (scalar) branch
+            asm volatile("" ::: "memory");
+            zero_excluded<E>(wq, chunk, &a_virt, 1);
+        }
         z[0] += chunk_sum<E>(wp);
         z[1] += chunk_sum<E>(wq);
     });
@@ -487,7 +490,8 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
             ep[e] = cp(pa_[e]);
             eq[e] = cq(qa_[e]);
         }
-        if (s == a_slab) {
+        if (__builtin_expect(s == a_slab, 0)) {
+            asm volatile("" ::: "memory");
             zero_excluded<E>(ep, chunk, &a_virt, 1);
             zero_excluded<E>(eq, chunk, &a_virt, 1);
         }
