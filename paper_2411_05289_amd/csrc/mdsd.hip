@@ -1009,13 +1009,46 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
             if (ov_slab[j] == i) v = ov_val[j];
         return v;
     };
+    // this lane's weights of one chunk of slab s, removed tokens counting 0: from memory when the
+    // row is streamed, from the registers of the wave that owns the slab when it is resident
     auto cw = [&](int s, float(&w)[E]) { chunk_weights<DT, CV>(rq, cq, excl, n_excl, s, w); };
+    auto cw_reg = [&](int it, float(&w)[E]) {
+        if constexpr (NIT > 0) {
+            float a[E];
+            get_dyn(sq, it, a);
+#pragma unroll
+            for (int e = 0; e < E; ++e) w[e] = cq(a[e]);
+            zero_excluded<E>(w, ((it * kWaves + wave_id()) * 64 + (int)(threadIdx.x & 63)), excl, n_excl);
+        }
+    };
+    auto draw = [&](float u, float W) {
+        if constexpr (NIT > 0) {
+            // draws with replacement follow each other with no barrier in between: the result
+            // slot in LDS must have been read by every wave before the next draw writes it
+            if constexpr (METHOD == kRRS) __syncthreads();
+            return __builtin_amdgcn_readfirstlane(draw_resident<E>(rq.nslab, u, W, sv, cw_reg, sh));
+        } else {
+            return icdf_slabs<E>(rq.nslab, u, W, sv, cw);
+        }
+    };
     auto remove_token = [&](int v) {
         excl[n_excl++] = v;
         const int s = v / (64 * E);
-        float w[E];
-        cw(s, w);
-        const float t = wave_sum(chunk_sum<E>(w));
+        float t;
+        if constexpr (NIT > 0) {
+            if (wave_id() == s % kWaves) {
+                float w[E];
+                cw_reg(s / kWaves, w);
+                const float ts = wave_sum(chunk_sum<E>(w));
+                if ((threadIdx.x & 63) == 0) sh.bcast_f = ts;
+            }
+            __syncthreads();
+            t = sh.bcast_f;
+        } else {
+            float w[E];
+            cw(s, w);
+            t = wave_sum(chunk_sum<E>(w));
+        }
         int j = 0;
         while (j < n_ov && ov_slab[j] != s) ++j;
         ov_slab[j] = s;
@@ -1026,14 +1059,14 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
     int out_tok[MDSD_MAX_K];
     if constexpr (METHOD == kSpecHub) {
         const float W = slab_total(rq.nslab, sv);
-        const int v = icdf_slabs<E>(rq.nslab, ur[0], W, sv, cw);
+        const int v = draw(ur[0], W);
         if (v != a_virt) {
             out_tok[0] = v < 0 ? -1 : v - rq.head;
             out_tok[1] = a_virt - rq.head;
         } else {
             remove_token(a_virt);
             const float W2 = slab_total(rq.nslab, sv);
-            int v2 = icdf_slabs<E>(rq.nslab, ur[1], W2, sv, cw);
+            int v2 = draw(ur[1], W2);
             if (v2 < 0) {
                 v2 = a_virt;
                 flags |= MDSD_FLAG_DEGENERATE_HUB;
@@ -1045,7 +1078,7 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
         int prev = rq.head;
         for (int i = 0; i < k; ++i) {
             const float W = slab_total(rq.nslab, sv);
-            int v = icdf_slabs<E>(rq.nslab, ur[i], W, sv, cw);
+            int v = draw(ur[i], W);
             if (v < 0) {
                 v = prev;
                 flags |= MDSD_FLAG_Q_EXHAUSTED;
