@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--copies", type=int, default=0, help="distinct input copies to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-stats", action="store_true",
+                    help="spechub_verify recomputes the draft row's hub and normalisers instead of "
+                         "taking them from spechub_draft")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 512 MiB device copy three times (reference dispatch for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -102,7 +105,7 @@ def main():
     pbs = [B.Problem.from_workload(w) for w in wls]
     u_d = [B.philox_uniform(args.seed + i, 1, Bn * N, k, device=dev).view(Bn, N, k) for i in range(copies)]
     u_v = [B.philox_uniform(args.seed + i, 2, Bn * N, k + 1, device=dev).view(Bn, N, k + 1) for i in range(copies)]
-    plans = [B.StepPlan(args.method, pbs[i], u_d[i], u_v[i]) for i in range(copies)]
+    plans = [B.StepPlan(args.method, pbs[i], u_d[i], u_v[i], hand_stats=not args.no_stats) for i in range(copies)]
     stream = B._stream()
 
     def step(i, ev=None):
@@ -150,7 +153,9 @@ def main():
         "config": {"workload": wl0.name, "method": args.method, "B": Bn, "nodes_per_tree": N, "V": wl0.V,
                    "k": k, "storage": wl0.dtype, "temperature": wl0.temp_target,
                    "step": "draft+verify+walk", "input_copies_rotated": copies,
-                   "early_exit": True, "tokens_per_step_last_batch": tps},
+                   "early_exit": True,
+                   "draft_stats_handed_to_verify": args.method == "spechub" and not args.no_stats,
+                   "tokens_per_step_last_batch": tps},
         "roofline": {"bound": "hbm", "kernel": "%s_verify" % args.method, "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": kernel_ms,

@@ -82,6 +82,27 @@ extern "C" {
 #define MDSD_FLAG_BAD_PAIR 8
 #define MDSD_FLAG_BAD_TOKEN 16
 
+/*
+ * Statistics of one draft row that both SpecHub calls need: the hub a (Sec. 4: the token of
+ * highest draft probability) and the two numbers that normalise q around it.  With
+ * pb->draft_stats set, spechub_draft writes one record per node (leaves: hub = -1) and
+ * spechub_verify reads them instead of scanning the draft row for them again; a node whose
+ * first acceptance test (Alg. 3, the non-hub token) succeeds then never reads its draft row.
+ * The records must come from spechub_draft on the same draft rows, dtype, kind and
+ * temp_draft: the library cannot check that.  A hub outside [0,V) makes the node
+ * MDSD_BAD_PAIR.  Only the kernels for logit rows that fit in registers use the records;
+ * every other path recomputes them from the rows, so results never depend on the pointer
+ * beyond fp32 rounding of rest_mass (a different summation order).
+ */
+typedef struct mdsd_row_stats {
+    float max_stored; /* largest stored element of the row (a logit, or a probability)        */
+    float rest_mass;  /* sum over y != hub of exp((l(y) - max_stored)/temp_draft) for logits,
+                         of q(y) for probabilities: the draft mass outside the hub, times the
+                         softmax normaliser when the hub's weight is 1                        */
+    int32_t hub;      /* argmax of the stored row, lowest index on ties; -1 on leaves         */
+    int32_t reserved; /* written as 0                                                         */
+} mdsd_row_stats;
+
 typedef struct mdsd_problem {
     const void* target;         /* device, [B,N,ld_t] rows of the target model            */
     const void* draft;          /* device, [B,N,ld_d] rows of the draft model             */
@@ -94,6 +115,8 @@ typedef struct mdsd_problem {
     int32_t k;                  /* children per internal node (drafts per step)           */
     int32_t depth;              /* levels of the tree = max tokens emitted per tree       */
     const int32_t* first_child; /* device [N] or NULL (complete k-ary tree)               */
+    mdsd_row_stats* draft_stats; /* device [B,N] or NULL: what spechub_draft learnt
+                                   about each draft row, handed on to spechub_verify (below) */
 } mdsd_problem;
 
 typedef struct mdsd_result {

@@ -8,6 +8,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
+import dataclasses
 from dataclasses import dataclass
 from typing import Optional
 
@@ -41,6 +42,7 @@ class _Problem(C.Structure):
         ("B", C.c_int32), ("N", C.c_int32), ("V", C.c_int32),
         ("k", C.c_int32), ("depth", C.c_int32),
         ("first_child", C.c_void_p),
+        ("draft_stats", C.c_void_p),
     ]
 
 
@@ -107,6 +109,16 @@ class Problem:
     temp_target: float = 1.0
     temp_draft: float = 1.0
     first_child: Optional[torch.Tensor] = None  # [N] int32 on device, or None
+    # [B,N,4] float32 on device, or None: one record per node (max stored draft element, draft
+    # mass outside the hub, hub index as int32 bits, 0) that spechub_draft writes and
+    # spechub_verify reads instead of scanning the draft row for them again
+    draft_stats: Optional[torch.Tensor] = None
+
+    def with_draft_stats(self) -> "Problem":
+        """The same problem with a fresh record array attached."""
+        B, N, _ = self.draft.shape
+        stats = torch.zeros((B, N, 4), dtype=torch.float32, device=self.draft.device)
+        return dataclasses.replace(self, draft_stats=stats)
 
     @staticmethod
     def from_workload(wl) -> "Problem":
@@ -156,6 +168,11 @@ def _c_problem(pb: Problem) -> _Problem:
         cp.first_child = pb.first_child.data_ptr()
     else:
         cp.first_child = None
+    if pb.draft_stats is not None:
+        _check_dev(pb.draft_stats, "draft_stats", torch.float32, (B, N, 4))
+        cp.draft_stats = pb.draft_stats.data_ptr()
+    else:
+        cp.draft_stats = None
     return cp
 
 
@@ -276,9 +293,11 @@ class StepPlan:
     three foreign calls per step and nothing else.  The tensors handed in must stay alive
     and in place for the life of the plan."""
 
-    def __init__(self, method: str, pb: Problem, u_draft, u_verify, *, flags=True):
+    def __init__(self, method: str, pb: Problem, u_draft, u_verify, *, flags=True, hand_stats=True):
         if method not in ("spechub", "rrs", "rrsw"):
             raise ValueError("unknown method %r" % method)
+        if method == "spechub" and hand_stats and pb.draft_stats is None:
+            pb = pb.with_draft_stats()   # spechub_draft -> spechub_verify hand-over of the row statistics
         B, N, _ = pb.draft.shape
         dev = pb.draft.device
         self.method, self.pb = method, pb

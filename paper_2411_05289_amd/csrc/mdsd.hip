@@ -40,6 +40,9 @@ struct Params {
     // draft kernels
     int32_t* tokens_out;
     int32_t* hub_out;
+    // draft-row statistics: written by the SpecHub draft kernel, read by the SpecHub verify kernel
+    mdsd_row_stats* stats_out;
+    const mdsd_row_stats* stats_in;
 };
 
 struct Shared {
@@ -335,9 +338,13 @@ struct NodeIn {
     bool tokens_ok;
     float lp1, lq1, lp2, lq2;
     float u0, u1, u2;
+    // only with statistics handed on by the draft call
+    int hub;          // token index, -1 = not usable
+    float q_max, q_rest;
+    float lpa;        // the target's stored logit at the hub
 };
 
-template <int DT>
+template <int DT, bool STATS>
 __device__ __forceinline__ void fetch_node_inputs(const Params& P, const NodeId& id, const RowView& rp,
                                                   const RowView& rq, NodeIn& in)
 {
@@ -348,6 +355,8 @@ __device__ __forceinline__ void fetch_node_inputs(const Params& P, const NodeId&
     in.x1 = in.x2 = -1;
     in.tokens_ok = false;
     in.lp1 = in.lq1 = in.lp2 = in.lq2 = 0.f;
+    in.hub = -1;
+    in.q_max = in.q_rest = in.lpa = 0.f;
     if (id.c0 >= 0) {
         const int32_t* xt = P.tokens + (int64_t)id.b * P.N + id.c0;
         in.x1 = xt[0];
@@ -359,14 +368,24 @@ __device__ __forceinline__ void fetch_node_inputs(const Params& P, const NodeId&
             in.lp2 = load_elem<DT>(rp, in.x2);
             in.lq2 = load_elem<DT>(rq, in.x2);
         }
+        if constexpr (STATS) {
+            const mdsd_row_stats st = P.stats_in[id.row];
+            in.q_max = st.max_stored;
+            in.q_rest = st.rest_mass;
+            in.hub = (st.hub >= 0 && st.hub < P.V) ? st.hub : -1;
+            if (in.hub >= 0) in.lpa = load_elem<DT>(rp, in.hub);
+        }
     }
 }
 
 // internal node, SpecHub (Alg. 3)
-template <int DT, int NIT, bool MASKED>
+// STATS: the hub and the draft row's normalisers come with the node (the draft call left
+// them); the draft row is then only needed for the residual sums, and is asked for only once
+// the first test has failed.
+template <int DT, int NIT, bool MASKED, bool STATS>
 __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& in, const RowView& rp,
                                                  const RowView& rq, const RowSrc<DT, NIT, MASKED>& sp,
-                                                 const RowSrc<DT, NIT, MASKED>& sq, bool need_full,
+                                                 RowSrc<DT, NIT, MASKED>& sq, bool need_full,
                                                  float* rprob, Shared& sh, int& phase, NodeOut& o)
 {
     constexpr int E = Elem<DT>::kPerChunk;
@@ -375,46 +394,78 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
     const bool tokens_ok = in.tokens_ok;
     const float u0 = in.u0, u1 = in.u1, u2 = in.u2;
 
-    // ---- maxima of the stored logits; hub = lowest index among the maxima of the draft row
-    const float mq_lane = lane_max(sq);
-    float mm[2] = {lane_max(sp), mq_lane};
-    block_max<kWaves, 2>(mm, sh.red, phase);
-    int my_idx = INT_MAX;
-    if (mq_lane == mm[1]) my_idx = lane_first_index_of(sq, mm[1]);
-    int a_virt = block_min_index<kWaves>(my_idx, sh.red, phase);
-    const bool owner = my_idx == a_virt && a_virt != INT_MAX;
-    if (a_virt == INT_MAX) a_virt = rq.head;  // a row of NaNs has no maximum: stay in bounds
-    a_virt = __builtin_amdgcn_readfirstlane(a_virt);
-    const int a = a_virt - rq.head;
-    if (owner) sh.bcast_f = own_element(sp, a_virt);  // the target's logit at the hub
+    float mm[2], z[2] = {0.f, 0.f};
+    int a_virt;
     ExpW cp, cq;
     cp.s = kLog2e / P.temp_target;
-    cp.ms = mm[0] * cp.s;
     cq.s = kLog2e / P.temp_draft;
-    cq.ms = mm[1] * cq.s;
-
-    // ---- normalisers: Zp and the draft mass outside the hub, Zq' = sum_{y != a} eq (summed
-    // without the hub, never formed as a difference)
-    const int a_slab = a_virt / (64 * E);
-    float z[2] = {0.f, 0.f};
-    for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
-        float wp[E], wq[E];
+    float lp_hub;
+    if constexpr (STATS) {
+        if (in.hub < 0) {  // no usable record for this node
+            o.flags |= MDSD_FLAG_BAD_PAIR;
+            o.outcome = MDSD_BAD_PAIR;
+            return;
+        }
+        // ---- target row alone: maximum, then Zp
+        float m1[1] = {lane_max(sp)};
+        block_max<kWaves, 1>(m1, sh.red, phase);
+        mm[0] = m1[0];
+        mm[1] = in.q_max;
+        a_virt = rq.head + in.hub;
+        cp.ms = mm[0] * cp.s;
+        cq.ms = mm[1] * cq.s;
+        float z1[1] = {0.f};
+        sp.for_each([&](int, int, const float(&pa_)[E]) {
+            float wp[E];
 #pragma unroll
-        for (int e = 0; e < E; ++e) {
-            wp[e] = cp(pa_[e]);
-            wq[e] = cq(qa_[e]);
-        }
-        if (__builtin_expect(s == a_slab, 0)) {  // one slab of the row: a real (scalar) branch
-            asm volatile("" ::: "memory");
-            zero_excluded<E>(wq, chunk, &a_virt, 1);
-        }
-        z[0] += chunk_sum<E>(wp);
-        z[1] += chunk_sum<E>(wq);
-    });
-    block_sum<kWaves, 2>(z, sh.red, phase);  // barrier: bcast_f visible
+            for (int e = 0; e < E; ++e) wp[e] = cp(pa_[e]);
+            z1[0] += chunk_sum<E>(wp);
+        });
+        block_sum<kWaves, 1>(z1, sh.red, phase);
+        z[0] = z1[0];
+        z[1] = in.q_rest;
+        lp_hub = in.lpa;
+    } else {
+        // ---- maxima of the stored logits; hub = lowest index among the maxima of the draft row
+        const float mq_lane = lane_max(sq);
+        mm[0] = lane_max(sp);
+        mm[1] = mq_lane;
+        block_max<kWaves, 2>(mm, sh.red, phase);
+        int my_idx = INT_MAX;
+        if (mq_lane == mm[1]) my_idx = lane_first_index_of(sq, mm[1]);
+        a_virt = block_min_index<kWaves>(my_idx, sh.red, phase);
+        const bool owner = my_idx == a_virt && a_virt != INT_MAX;
+        if (a_virt == INT_MAX) a_virt = rq.head;  // a row of NaNs has no maximum: stay in bounds
+        a_virt = __builtin_amdgcn_readfirstlane(a_virt);
+        if (owner) sh.bcast_f = own_element(sp, a_virt);  // the target's logit at the hub
+        cp.ms = mm[0] * cp.s;
+        cq.ms = mm[1] * cq.s;
+
+        // ---- normalisers: Zp and the draft mass outside the hub, Zq' = sum_{y != a} eq (summed
+        // without the hub, never formed as a difference)
+        const int hub_slab = a_virt / (64 * E);
+        for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
+            float wp[E], wq[E];
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                wp[e] = cp(pa_[e]);
+                wq[e] = cq(qa_[e]);
+            }
+            if (__builtin_expect(s == hub_slab, 0)) {  // one slab of the row: a real (scalar) branch
+                asm volatile("" ::: "memory");
+                zero_excluded<E>(wq, chunk, &a_virt, 1);
+            }
+            z[0] += chunk_sum<E>(wp);
+            z[1] += chunk_sum<E>(wq);
+        });
+        block_sum<kWaves, 2>(z, sh.red, phase);  // barrier: bcast_f visible
+        lp_hub = sh.bcast_f;
+    }
+    const int a = a_virt - rq.head;
+    const int a_slab = a_virt / (64 * E);
     const float Zq_rest = z[1];
     const float ea_q = cq(mm[1]);
-    const float ea_p = cp(sh.bcast_f);
+    const float ea_p = cp(lp_hub);
     HubScal h;
     h.iZp = 1.f / z[0];
     h.iZq = 1.f / (Zq_rest + ea_q);
@@ -482,6 +533,7 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
     }
 
     // ---- residual sums: S_xa = sum Q'(.,a), S_ax = sum Q'(a,.), slab sums of p''
+    if constexpr (STATS) sq.issue(rq, ExpW::fill());
     float sacc[2] = {0.f, 0.f};
     for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
         float ep[E], eq[E], t_xa[E], t_ax[E], w[E];
@@ -559,7 +611,7 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
 
 // SpecHub verify for logit rows that fit in registers: one workgroup per node, every load of the
 // node queued before anything waits, all passes from registers.
-template <int DT, int NIT, bool MASKED>
+template <int DT, int NIT, bool MASKED, bool STATS>
 __global__ __launch_bounds__(kWG, (NIT <= 8 ? 4 : 2)) void spechub_verify_resident(const Params P)
 {
     __shared__ Shared sh;
@@ -573,15 +625,15 @@ __global__ __launch_bounds__(kWG, (NIT <= 8 ? 4 : 2)) void spechub_verify_reside
     sp.issue(rp, ExpW::fill());
     if (id.c0 >= 0) {
         rq = make_row<DT>(P.draft, P.ld_d, id.row, P.V);
-        sq.issue(rq, ExpW::fill());
+        if constexpr (!STATS) sq.issue(rq, ExpW::fill());
     }
     NodeIn in;
-    fetch_node_inputs<DT>(P, id, rp, rq, in);
+    fetch_node_inputs<DT, STATS>(P, id, rp, rq, in);
     NodeOut o{MDSD_NONE, -1, 0, 0.f};
     if (id.c0 < 0)
         leaf_resident<DT, NIT, MASKED>(P, rp, sp, in.u2, rprob, sh, phase, o);
     else
-        spechub_resident<DT, NIT, MASKED>(P, in, rp, rq, sp, sq, need_full, rprob, sh, phase, o);
+        spechub_resident<DT, NIT, MASKED, STATS>(P, in, rp, rq, sp, sq, need_full, rprob, sh, phase, o);
     if (threadIdx.x == 0) {
         P.outcome[id.row] = o.outcome;
         P.token[id.row] = o.token;
@@ -971,6 +1023,7 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
         if (threadIdx.x == 0) {
             if (P.hub_out) P.hub_out[row] = -1;
             if (P.flags) P.flags[row] = 0;
+            if (P.stats_out) P.stats_out[row] = mdsd_row_stats{0.f, 0.f, -1, 0};
         }
         return;
     }
@@ -984,9 +1037,10 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
 
     CV cq{0.f, 0.f};
     int a_virt = rq.head;
+    float mm[1] = {0.f};
     if (LOGITS || METHOD == kSpecHub) {
         const float mq_lane = lane_max(sq);
-        float mm[1] = {mq_lane};
+        mm[0] = mq_lane;
         block_max<kWaves, 1>(mm, sh.red, phase);
         if constexpr (METHOD == kSpecHub) a_virt = block_argmax(sq, mq_lane, mm[0], sh, phase);
         if constexpr (LOGITS) {
@@ -1060,12 +1114,18 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
     if constexpr (METHOD == kSpecHub) {
         const float W = slab_total(rq.nslab, sv);
         const int v = draw(ur[0], W);
+        // the mass outside the hub: for the second draw, and for the verify call if it asked
+        float W2 = 0.f;
+        if (v == a_virt || P.stats_out) {
+            remove_token(a_virt);
+            W2 = slab_total(rq.nslab, sv);
+            if (P.stats_out && threadIdx.x == 0)
+                P.stats_out[row] = mdsd_row_stats{mm[0], W2, a_virt - rq.head, 0};
+        }
         if (v != a_virt) {
             out_tok[0] = v < 0 ? -1 : v - rq.head;
             out_tok[1] = a_virt - rq.head;
         } else {
-            remove_token(a_virt);
-            const float W2 = slab_total(rq.nslab, sv);
             int v2 = draw(ur[1], W2);
             if (v2 < 0) {
                 v2 = a_virt;
@@ -1248,11 +1308,17 @@ static void launch_verify_n(int nit, dim3 grid, dim3 block, hipStream_t st, cons
 template <int DT>
 static void launch_spechub_resident(int nit, bool masked, dim3 grid, dim3 block, hipStream_t st, const Params& P)
 {
-#define MDSD_LAUNCH_RES(N)                                                                          \
-    if (masked)                                                                                     \
-        hipLaunchKernelGGL((spechub_verify_resident<DT, N, true>), grid, block, 0, st, P);          \
+#define MDSD_LAUNCH_RES2(N, M)                                                                      \
+    if (P.stats_in)                                                                                 \
+        hipLaunchKernelGGL((spechub_verify_resident<DT, N, M, true>), grid, block, 0, st, P);       \
     else                                                                                            \
-        hipLaunchKernelGGL((spechub_verify_resident<DT, N, false>), grid, block, 0, st, P)
+        hipLaunchKernelGGL((spechub_verify_resident<DT, N, M, false>), grid, block, 0, st, P)
+#define MDSD_LAUNCH_RES(N)                                                                          \
+    if (masked) {                                                                                   \
+        MDSD_LAUNCH_RES2(N, true);                                                                  \
+    } else {                                                                                        \
+        MDSD_LAUNCH_RES2(N, false);                                                                 \
+    }
     if (nit == 4) {
         MDSD_LAUNCH_RES(4);
     } else if (nit == 8) {
@@ -1260,6 +1326,7 @@ static void launch_spechub_resident(int nit, bool masked, dim3 grid, dim3 block,
     } else {
         MDSD_LAUNCH_RES(16);
     }
+#undef MDSD_LAUNCH_RES2
 #undef MDSD_LAUNCH_RES
 }
 
@@ -1354,6 +1421,7 @@ static int verify_entry(int method, const mdsd_problem* pb, const int32_t* token
     P.resid_mass = out->resid_mass;
     P.flags = out->flags;
     P.resid_prob = out->resid_prob;
+    P.stats_in = method == kSpecHub ? pb->draft_stats : nullptr;
     hipStream_t st = (hipStream_t)stream;
     (void)hipGetLastError();
     if (method == kSpecHub)
@@ -1378,6 +1446,7 @@ static int draft_entry(int method, const mdsd_problem* pb, const float* u, int32
     P.tokens_out = tokens;
     P.hub_out = hub;
     P.flags = flags;
+    P.stats_out = method == kSpecHub ? pb->draft_stats : nullptr;
     hipStream_t st = (hipStream_t)stream;
     (void)hipGetLastError();
     if (method == kSpecHub)

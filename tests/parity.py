@@ -114,6 +114,23 @@ def check_case(method: str, wl: Workload, seed: int = 0, seqs=None, full_outputs
             bad = (diff > tol) & ok_nodes[:, :, None]
             assert not bad.any(), "resid_prob off at %s (diff %g)" % (np.argwhere(bad)[:5], diff[bad].max())
             out["resid_prob_max_abs"] = float(diff[ok_nodes].max(initial=0.0))
+    if method == "spechub":
+        # ---- the same two stages with the draft call's row statistics handed to verify
+        pb_s = pb.with_draft_stats()
+        g_ds = DRAFT[method](pb_s, u_d)
+        assert torch.equal(g_ds["tokens"], g_d["tokens"]) and torch.equal(g_ds["hub"], g_d["hub"])
+        _check_stats(wl, _np(pb_s.draft_stats[idx]), d_np, o_d["hub"], internal)
+        g_s = VERIFY[method](pb_s, tokens, u_v, resid_mass=False, flags=True, walk=True)
+        out["mismatch_in_band_stats"] = _compare_nodes(g_s, o_v, idx, near, "early-exit+stats", ctx)
+        _compare_walk(wl, g_s, o_v, idx, near)
+        assert out["mismatch_in_band_stats"] <= 2 + 0.02 * near.size, out
+        if full_outputs:
+            g_sf = VERIFY[method](pb_s, tokens, u_v, resid_mass=True, flags=True, walk=True)
+            _compare_nodes(g_sf, o_v, idx, near, "full+stats", ctx)
+            rm_g = _np(g_sf["resid_mass"][idx]).astype(np.float64)
+            valid = _np(g_sf["outcome"][idx]) >= -1
+            bad = valid & (np.abs(rm_g - o_v["resid_mass"]) > 1e-5 * np.abs(o_v["resid_mass"]) + RESID_MASS_ATOL)
+            assert not bad.any(), "resid_mass (stats) off at %s" % (np.argwhere(bad)[:5],)
     if report is not None:
         report.append((method, wl.name, out))
     # An inverse-CDF draw lands within 1e-6 of a token boundary whenever it hits a token of
@@ -121,6 +138,26 @@ def check_case(method: str, wl: Workload, seed: int = 0, seqs=None, full_outputs
     # the nodes where the two sides then really differ must stay a small fraction.
     assert out["mismatch_in_band"] <= 2 + 0.02 * near.size, out
     return out
+
+
+def _check_stats(wl: Workload, stats, d_np, hub, internal):
+    """Records left by spechub_draft: hub index, the row's largest stored element, and the
+    draft mass outside the hub (unnormalised for logits), against fp64 sums over the rows."""
+    st_hub = stats[..., 2].copy().view(np.int32)
+    assert (st_hub[:, internal] == hub[:, internal]).all(), "stats hub differs"
+    assert (st_hub[:, ~internal] == -1).all()
+    rows = _to_f64(d_np, wl.dtype)[:, internal]
+    a = hub[:, internal]
+    m = rows.max(axis=-1)
+    assert (stats[..., 0][:, internal].astype(np.float64) == m).all(), "stats max differs"
+    if wl.kind == "logits":
+        w = np.exp((rows - m[..., None]) / np.float64(np.float32(wl.temp_draft)))
+    else:
+        w = rows.copy()
+    np.put_along_axis(w, a[..., None], 0.0, axis=-1)
+    rest = w.sum(axis=-1)
+    got = stats[..., 1][:, internal].astype(np.float64)
+    assert np.allclose(got, rest, rtol=1e-5, atol=1e-30), "stats rest_mass off: %g" % np.abs(got / rest - 1).max()
 
 
 def _internal_mask(wl: Workload):
