@@ -23,6 +23,13 @@ namespace mdsd {
 
 enum Method { kSpecHub = 0, kRRS = 1, kRRSw = 2 };
 
+#ifndef MDSD_QW
+#define MDSD_QW 2
+#endif
+#ifndef MDSD_STATS_WAVES
+#define MDSD_STATS_WAVES 6
+#endif
+
 struct Params {
     const void* target;
     const void* draft;
@@ -533,9 +540,8 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
     }
 
     // ---- residual sums: S_xa = sum Q'(.,a), S_ax = sum Q'(a,.), slab sums of p''
-    if constexpr (STATS) sq.issue(rq, ExpW::fill());
     float sacc[2] = {0.f, 0.f};
-    for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
+    auto residual_terms = [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
         float ep[E], eq[E], t_xa[E], t_ax[E], w[E];
 #pragma unroll
         for (int e = 0; e < E; ++e) {
@@ -552,7 +558,11 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
         sacc[0] += chunk_sum<E>(t_xa);
         sacc[1] += chunk_sum<E>(t_ax);
         store_slab_sum(sh.slab_w, s, chunk_sum<E>(w));
-    });
+    };
+    if constexpr (STATS)
+        for_each_streamed<MDSD_QW>(sp, rq, ExpW::fill(), residual_terms);  // the draft row's only read
+    else
+        for_each2(sp, sq, residual_terms);
     block_sum<kWaves, 2>(sacc, sh.red, phase);  // barrier: slab sums visible
     const float S_xa = sacc[0], S_ax = sacc[1];
     if (!decided) {
@@ -573,7 +583,14 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
     o.rmass = W;
     bool wrote_prob = false;
     if (!decided) {
-        int v = draw_resident<E>(rp.nslab, u2, W, sv, [&](int it, float(&w)[E]) {
+        int v;
+        if constexpr (STATS)
+            // the drawn slab's share of the draft row comes from memory a second time (1 KiB)
+            v = icdf_slabs<E>(rp.nslab, u2, W, sv, [&](int s, float(&w)[E]) {
+                spechub_chunk_w<DT, ExpW>(rp, rq, cp, cq, h, a_virt, s, w);
+            });
+        else
+            v = draw_resident<E>(rp.nslab, u2, W, sv, [&](int it, float(&w)[E]) {
             float a_[E], b_[E];
             get_dyn(sp, it, a_);
             get_dyn(sq, it, b_);
@@ -612,7 +629,7 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
 // SpecHub verify for logit rows that fit in registers: one workgroup per node, every load of the
 // node queued before anything waits, all passes from registers.
 template <int DT, int NIT, bool MASKED, bool STATS>
-__global__ __launch_bounds__(kWG, (NIT <= 8 ? 4 : 2)) void spechub_verify_resident(const Params P)
+__global__ __launch_bounds__(kWG, (NIT <= 8 ? (STATS ? MDSD_STATS_WAVES : 4) : 2)) void spechub_verify_resident(const Params P)
 {
     __shared__ Shared sh;
     int phase = 0;

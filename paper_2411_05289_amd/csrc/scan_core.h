@@ -173,6 +173,47 @@ __device__ __forceinline__ void for_each2(const RowSrc<DT, NIT, MASKED>& sa, con
     }
 }
 
+// body(slab, chunk, a[E], b[E]) with row a in registers and row b read from memory as the loop
+// goes, QW chunks ahead of their use; b is read exactly once and never held whole
+template <int QW, int DT, int NIT, bool MASKED, class Body>
+__device__ __forceinline__ void for_each_streamed(const RowSrc<DT, NIT, MASKED>& sa, const RowView& rb,
+                                                  float fill_b, Body body)
+{
+    static_assert(NIT > 0 && QW > 0, "row a must be resident");
+    constexpr int E = Elem<DT>::kPerChunk;
+    const int lane = threadIdx.x & 63, wave = wave_id();
+    const uint32_t fb = __builtin_bit_cast(uint32_t, fill_b);
+    const uint32_t fw = DT == 0 ? fb : ((fb >> 16) | (fb & 0xffff0000u));
+    auto fetch = [&](int it) {
+        const int chunk = (it * kWaves + wave) * 64 + lane;
+        return chunk < rb.nchunk ? load16(rb.chunks, chunk) : make_uint4(fw, fw, fw, fw);
+    };
+    uint4 win[QW];
+#pragma unroll
+    for (int i = 0; i < QW && i < NIT; ++i) win[i] = fetch(i);
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int s = it * kWaves + wave;
+        const uint4 cur = win[it % QW];
+        if (it + QW < NIT) win[it % QW] = fetch(it + QW);
+        if (s < sa.r.nslab) {
+            float a[E], b[E];
+            sa.get(it, a);
+            unpack<DT>(cur, b);
+            if constexpr (MASKED) {
+                const int v0 = (s * 64 + lane) * E;
+                if (v0 < rb.head || v0 + E > rb.nvirt) {
+#pragma unroll
+                    for (int e = 0; e < E; ++e)
+                        if (v0 + e < rb.head || v0 + e >= rb.nvirt) b[e] = fill_b;
+                }
+            }
+            body(s, s * 64 + lane, a, b);
+        }
+        __builtin_amdgcn_sched_barrier(0);  // one chunk pair at a time
+    }
+}
+
 // store one slab's sum: every lane passes its chunk sum, lane 63 writes
 __device__ __forceinline__ void store_slab_sum(float* slab_w, int s, float lane_sum)
 {
