@@ -11,6 +11,7 @@
 //   draw    inverse-CDF search over the slab sums, then inside one slab
 // Scalar look-ups of p(x), q(x) at the draft tokens sit between them.
 #include <hip/hip_runtime.h>
+#include <type_traits>
 #include <limits.h>
 #include <stdlib.h>
 #include <stdint.h>
@@ -351,9 +352,13 @@ struct NodeIn {
     float lpa;        // the target's stored logit at the hub
 };
 
-template <int DT, bool STATS>
-__device__ __forceinline__ void fetch_node_inputs(const Params& P, const NodeId& id, const RowView& rp,
-                                                  const RowView& rq, NodeIn& in)
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ float uniform(float v) { return as_f(__builtin_amdgcn_readfirstlane(as_i(v))); }
+
+// first the loads that depend on nothing but the node: uniforms, the pair, the record the
+// draft call left
+template <bool STATS>
+__device__ __forceinline__ void fetch_node_scalars(const Params& P, const NodeId& id, NodeIn& in)
 {
     const float* ur = P.u + id.row * 3;
     in.u0 = ur[0];
@@ -369,6 +374,21 @@ __device__ __forceinline__ void fetch_node_inputs(const Params& P, const NodeId&
         in.x1 = xt[0];
         in.x2 = xt[1];
         in.tokens_ok = in.x1 >= 0 && in.x1 < P.V && in.x2 >= 0 && in.x2 < P.V;
+        if constexpr (STATS) {
+            const mdsd_row_stats st = P.stats_in[id.row];
+            in.q_max = st.max_stored;
+            in.q_rest = st.rest_mass;
+            in.hub = (st.hub >= 0 && st.hub < P.V) ? st.hub : -1;
+        }
+    }
+}
+
+// then the stored logits at the tokens those loads named
+template <int DT, bool STATS>
+__device__ __forceinline__ void fetch_node_lookups(const NodeId& id, const RowView& rp, const RowView& rq,
+                                                   NodeIn& in)
+{
+    if (id.c0 >= 0) {
         if (in.tokens_ok) {
             in.lp1 = load_elem<DT>(rp, in.x1);
             in.lq1 = load_elem<DT>(rq, in.x1);
@@ -376,13 +396,17 @@ __device__ __forceinline__ void fetch_node_inputs(const Params& P, const NodeId&
             in.lq2 = load_elem<DT>(rq, in.x2);
         }
         if constexpr (STATS) {
-            const mdsd_row_stats st = P.stats_in[id.row];
-            in.q_max = st.max_stored;
-            in.q_rest = st.rest_mass;
-            in.hub = (st.hub >= 0 && st.hub < P.V) ? st.hub : -1;
             if (in.hub >= 0) in.lpa = load_elem<DT>(rp, in.hub);
         }
     }
+}
+
+template <int DT, bool STATS>
+__device__ __forceinline__ void fetch_node_inputs(const Params& P, const NodeId& id, const RowView& rp,
+                                                  const RowView& rq, NodeIn& in)
+{
+    fetch_node_scalars<STATS>(P, id, in);
+    fetch_node_lookups<DT, STATS>(id, rp, rq, in);
 }
 
 // internal node, SpecHub (Alg. 3)
@@ -513,6 +537,12 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
             o.outcome = 1;
             o.token = x2;
             decided = true;
+        } else if (u1 * qa < pa) {
+            // the hub's test u1 * S_ax < p(a) needs no sum when it already holds for the
+            // largest value S_ax can take: S_ax <= sum_{y != a} Q(a,y) = q(a)
+            o.outcome = 0;
+            o.token = a;
+            decided = true;
         }
     } else {
         o.flags |= MDSD_FLAG_BAD_PAIR;
@@ -559,10 +589,51 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
         sacc[1] += chunk_sum<E>(t_ax);
         store_slab_sum(sh.slab_w, s, chunk_sum<E>(w));
     };
-    if constexpr (STATS)
-        for_each_streamed<MDSD_QW>(sp, rq, ExpW::fill(), residual_terms);  // the draft row's only read
-    else
+    if constexpr (STATS) {
+        // the draft row's only read.  Half a chunk at a time, so that few values are live at once.
+        for_each_streamed<MDSD_QW>(sp, rq, ExpW::fill(), [&](int s, int chunk, const uint4& dp, const uint4& dq) {
+            constexpr int HE = E / 2;
+            float part[3][2];
+            auto half = [&](auto H) {
+                constexpr int hv = decltype(H)::value;
+                float ep[HE], eq[HE];
+                unpack_half<DT, MASKED, hv>(dp, rp, ExpW::fill(), chunk, ep);
+                unpack_half<DT, MASKED, hv>(dq, rq, ExpW::fill(), chunk, eq);
+#pragma unroll
+                for (int e = 0; e < HE; ++e) {
+                    ep[e] = cp(ep[e]);
+                    eq[e] = cq(eq[e]);
+                }
+                if (__builtin_expect(s == a_slab, 0)) {
+                    asm volatile("" ::: "memory");
+#pragma unroll
+                    for (int e = 0; e < HE; ++e)
+                        if (chunk * E + hv * HE + e == a_virt) ep[e] = eq[e] = 0.f;
+                }
+                float t_xa[HE], t_ax[HE], w[HE];
+#pragma unroll
+                for (int e = 0; e < HE; ++e) spechub_terms(ep[e], eq[e], h, t_xa[e], t_ax[e], w[e]);
+                // the two halves of chunk_sum's tree
+                if constexpr (HE == 4) {
+                    part[0][hv] = (t_xa[0] + t_xa[1]) + (t_xa[2] + t_xa[3]);
+                    part[1][hv] = (t_ax[0] + t_ax[1]) + (t_ax[2] + t_ax[3]);
+                    part[2][hv] = (w[0] + w[1]) + (w[2] + w[3]);
+                } else {
+                    part[0][hv] = t_xa[0] + t_xa[1];
+                    part[1][hv] = t_ax[0] + t_ax[1];
+                    part[2][hv] = w[0] + w[1];
+                }
+            };
+            half(std::integral_constant<int, 0>{});
+            __builtin_amdgcn_sched_barrier(0);
+            half(std::integral_constant<int, 1>{});
+            sacc[0] += part[0][0] + part[0][1];
+            sacc[1] += part[1][0] + part[1][1];
+            store_slab_sum(sh.slab_w, s, part[2][0] + part[2][1]);
+        });
+    } else {
         for_each2(sp, sq, residual_terms);
+    }
     block_sum<kWaves, 2>(sacc, sh.red, phase);  // barrier: slab sums visible
     const float S_xa = sacc[0], S_ax = sacc[1];
     if (!decided) {
@@ -783,6 +854,11 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
                 if (ur[0] * (h.c * qx) < fmaxf(px - qx, 0.f)) {  // pair (a, x): min(p'(x)/Q(a,x), 1)
                     outcome = 1;
                     token = x2;
+                    decided = true;
+                } else if (ur[1] * qa < pa) {
+                    // S_ax <= sum_{y != a} Q(a,y) = q(a): the hub's test holds whatever the sum is
+                    outcome = 0;
+                    token = a;
                     decided = true;
                 }
             } else {

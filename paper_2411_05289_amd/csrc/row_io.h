@@ -28,9 +28,13 @@ template <> struct Elem<1> {  // bf16
 typedef uint32_t v4u32 __attribute__((ext_vector_type(4)));
 typedef const MDSD_GLOBAL v4u32* GlobalChunks;
 
+// chunk i >= 0 of a row (rows are far smaller than 4 GiB): an unsigned 32-bit byte offset on
+// the row's address lets the load take the row pointer from scalar registers and keep one
+// vector register per address instead of two
 __device__ __forceinline__ uint4 load16(GlobalChunks p, int i)
 {
-    const v4u32 v = p[i];
+    const MDSD_GLOBAL char* b = reinterpret_cast<const MDSD_GLOBAL char*>(p);
+    const v4u32 v = *reinterpret_cast<GlobalChunks>(b + (uint32_t)i * 16u);
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 

@@ -173,14 +173,41 @@ __device__ __forceinline__ void for_each2(const RowSrc<DT, NIT, MASKED>& sa, con
     }
 }
 
-// body(slab, chunk, a[E], b[E]) with row a in registers and row b read from memory as the loop
-// goes, QW chunks ahead of their use; b is read exactly once and never held whole
+// half H (0 or 1) of a 16-byte chunk as floats; `chunk` is its number in row r, whose masked
+// elements read as `fill`
+template <int DT, bool MASKED, int H>
+__device__ __forceinline__ void unpack_half(const uint4& d, const RowView& r, float fill, int chunk,
+                                            float (&v)[Elem<DT>::kPerChunk / 2])
+{
+    constexpr int E = Elem<DT>::kPerChunk, HE = E / 2;
+    const uint32_t w0 = H == 0 ? d.x : d.z, w1 = H == 0 ? d.y : d.w;
+    if constexpr (DT == 0) {
+        v[0] = __builtin_bit_cast(float, w0);
+        v[1] = __builtin_bit_cast(float, w1);
+    } else {
+        v[0] = __builtin_bit_cast(float, w0 << 16);
+        v[1] = __builtin_bit_cast(float, w0 & 0xffff0000u);
+        v[2] = __builtin_bit_cast(float, w1 << 16);
+        v[3] = __builtin_bit_cast(float, w1 & 0xffff0000u);
+    }
+    if constexpr (MASKED) {
+        const int v0 = chunk * E + H * HE;
+        if (v0 < r.head || v0 + HE > r.nvirt) {
+#pragma unroll
+            for (int e = 0; e < HE; ++e)
+                if (v0 + e < r.head || v0 + e >= r.nvirt) v[e] = fill;
+        }
+    }
+}
+
+// body(slab, chunk, a, b) with the packed chunks of row a (in registers) and of row b, which is
+// read from memory as the loop goes, QW chunks ahead of their use: b is read exactly once and
+// never held whole.  Chunks of b past the end of the row read as `fill_b`.
 template <int QW, int DT, int NIT, bool MASKED, class Body>
 __device__ __forceinline__ void for_each_streamed(const RowSrc<DT, NIT, MASKED>& sa, const RowView& rb,
                                                   float fill_b, Body body)
 {
     static_assert(NIT > 0 && QW > 0, "row a must be resident");
-    constexpr int E = Elem<DT>::kPerChunk;
     const int lane = threadIdx.x & 63, wave = wave_id();
     const uint32_t fb = __builtin_bit_cast(uint32_t, fill_b);
     const uint32_t fw = DT == 0 ? fb : ((fb >> 16) | (fb & 0xffff0000u));
@@ -196,20 +223,7 @@ __device__ __forceinline__ void for_each_streamed(const RowSrc<DT, NIT, MASKED>&
         const int s = it * kWaves + wave;
         const uint4 cur = win[it % QW];
         if (it + QW < NIT) win[it % QW] = fetch(it + QW);
-        if (s < sa.r.nslab) {
-            float a[E], b[E];
-            sa.get(it, a);
-            unpack<DT>(cur, b);
-            if constexpr (MASKED) {
-                const int v0 = (s * 64 + lane) * E;
-                if (v0 < rb.head || v0 + E > rb.nvirt) {
-#pragma unroll
-                    for (int e = 0; e < E; ++e)
-                        if (v0 + e < rb.head || v0 + e >= rb.nvirt) b[e] = fill_b;
-                }
-            }
-            body(s, s * 64 + lane, a, b);
-        }
+        if (s < sa.r.nslab) body(s, s * 64 + lane, sa.d[it], cur);
         __builtin_amdgcn_sched_barrier(0);  // one chunk pair at a time
     }
 }
