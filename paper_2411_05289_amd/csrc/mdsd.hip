@@ -315,15 +315,30 @@ __device__ __forceinline__ void leaf_resident(const Params& P, const RowView& rp
                                               Shared& sh, int& phase, NodeOut& o)
 {
     constexpr int E = Elem<DT>::kPerChunk;
-    float mm[1] = {lane_max(sp)};
-    block_max<kWaves, 1>(mm, sh.red, phase);
+    using Src = RowSrc<DT, NIT, MASKED>;
     ExpW cp;
     cp.s = kLog2e / P.temp_target;
-    cp.ms = mm[0] * cp.s;
-    pass_weights_to_slabs<ExpW>(sp, cp, nullptr, 0, sh.slab_w);
-    __syncthreads();
     auto sv = [&](int i) { return sh.slab_w[i]; };
-    const float W = slab_total(rp.nslab, sv);
+    float W;
+    // the cheap estimate of the maximum as the shift where there is one; if the weights
+    // overflowed or vanished with it, once more with the maximum itself
+    auto slab_sums = [&](float lane_m) {
+        float mm[1] = {lane_m};
+        block_max<kWaves, 1>(mm, sh.red, phase);
+        cp.ms = mm[0] * cp.s;
+        pass_weights_to_slabs<ExpW>(sp, cp, nullptr, 0, sh.slab_w);
+        __syncthreads();
+        return slab_total(rp.nslab, sv);
+    };
+    if constexpr (Src::kHasShiftEstimate) {
+        W = slab_sums(sp.lane_shift_estimate());
+        if (__builtin_expect(!(W > 0.f && W < __builtin_inff()), 0)) {
+            __syncthreads();  // every wave has read the slab sums that are about to be rewritten
+            W = slab_sums(lane_max(sp));
+        }
+    } else {
+        W = slab_sums(lane_max(sp));
+    }
     const int v = draw_resident<E>(rp.nslab, u, W, sv, [&](int it, float(&w)[E]) {
         float a[E];
         get_dyn(sp, it, a);
@@ -437,22 +452,33 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
             o.outcome = MDSD_BAD_PAIR;
             return;
         }
-        // ---- target row alone: maximum, then Zp
-        float m1[1] = {lane_max(sp)};
-        block_max<kWaves, 1>(m1, sh.red, phase);
-        mm[0] = m1[0];
+        // ---- target row alone: shift (the cheap estimate of the maximum first, the maximum
+        // itself if the weights overflowed or vanished with it), then Zp
+        using Src = RowSrc<DT, NIT, MASKED>;
         mm[1] = in.q_max;
         a_virt = rq.head + in.hub;
-        cp.ms = mm[0] * cp.s;
         cq.ms = mm[1] * cq.s;
-        float z1[1] = {0.f};
-        sp.for_each([&](int, int, const float(&pa_)[E]) {
-            float wp[E];
+        float z1[1];
+        auto normaliser = [&](float lane_m) {
+            float m1[1] = {lane_m};
+            block_max<kWaves, 1>(m1, sh.red, phase);
+            mm[0] = m1[0];
+            cp.ms = mm[0] * cp.s;
+            z1[0] = 0.f;
+            sp.for_each([&](int, int, const float(&pa_)[E]) {
+                float wp[E];
 #pragma unroll
-            for (int e = 0; e < E; ++e) wp[e] = cp(pa_[e]);
-            z1[0] += chunk_sum<E>(wp);
-        });
-        block_sum<kWaves, 1>(z1, sh.red, phase);
+                for (int e = 0; e < E; ++e) wp[e] = cp(pa_[e]);
+                z1[0] += chunk_sum<E>(wp);
+            });
+            block_sum<kWaves, 1>(z1, sh.red, phase);
+        };
+        if constexpr (Src::kHasShiftEstimate) {
+            normaliser(sp.lane_shift_estimate());
+            if (__builtin_expect(!(z1[0] > 0.f && z1[0] < __builtin_inff()), 0)) normaliser(lane_max(sp));
+        } else {
+            normaliser(lane_max(sp));
+        }
         z[0] = z1[0];
         z[1] = in.q_rest;
         lp_hub = in.lpa;
@@ -528,6 +554,12 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
         if (u0 * qx < px) {  // pair (x, a): min(p(x)/Q(x,a), 1)
             o.outcome = 0;
             o.token = x1;
+            decided = true;
+        } else if (u1 * (Zq_rest * h.iZq) < pa - qa) {
+            // the hub's test u1 * S_xa < p(a) - S_ax needs no sum when it holds for the bounds
+            // S_xa <= sum_{y != a} q(y) and S_ax <= q(a)
+            o.outcome = 1;
+            o.token = a;
             decided = true;
         }
     } else if (x1 == a && x2 != a) {

@@ -117,6 +117,27 @@ struct RowSrc {
             }
         }
     }
+
+    // A softmax shift for a quarter of the work of an exact maximum.  bf16 rows that need no
+    // masking only: the largest 32-bit word of this lane's chunks read as a float, which is the
+    // odd-indexed element with its neighbour's bits as extra mantissa (less than one bf16 ulp
+    // away from it).  The even-indexed elements may lie above it: whoever shifts by this
+    // value checks that the sum of the weights stayed finite and positive, and takes the
+    // exact maximum if not.
+    static constexpr bool kHasShiftEstimate = DT == 1 && !MASKED;
+    __device__ __forceinline__ float lane_shift_estimate() const
+    {
+        const int lane = threadIdx.x & 63, wave = wave_id();
+        float m = -__builtin_inff();
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            if ((it * kWaves + wave) * 64 + lane < r.nchunk) {
+                m = fmaxf(fmaxf(m, __builtin_bit_cast(float, d[it].x)), __builtin_bit_cast(float, d[it].y));
+                m = fmaxf(fmaxf(m, __builtin_bit_cast(float, d[it].z)), __builtin_bit_cast(float, d[it].w));
+            }
+        }
+        return m;
+    }
 };
 
 template <int DT, bool MASKED>

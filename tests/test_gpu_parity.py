@@ -128,6 +128,30 @@ def test_temperatures(method, T, request):
     note(request, check_case(method, wl, seed=int(T * 10)))
 
 
+def test_rows_with_isolated_peaks(request):
+    """bf16 rows whose largest logits sit far above the rest at even and at odd token indices
+    (a shift taken from every second element would overflow or underflow the weights), and
+    rows holding -inf (masked tokens): the softmax must still be the exact one."""
+    wl = W.config(3, device=DEV, B=6, V=4096, seed=31)
+    g = torch.Generator(device="cpu").manual_seed(31)
+    # the target's peaks leave every other weight at zero in fp32; the draft's stay moderate, so
+    # that its mass outside the hub does not vanish in fp32 while it is positive in fp64
+    for rows, peak in ((wl.target, 300.0), (wl.draft, 40.0)):
+        Bn, N, V = rows.shape
+        for b in range(Bn):
+            for n in range(N):
+                kind = (b * N + n) % 4
+                if kind == 0:      # one dominant token at an even index
+                    rows[b, n, 2 * int(torch.randint(0, V // 2, (1,), generator=g))] = peak
+                elif kind == 1:    # at an odd index
+                    rows[b, n, 2 * int(torch.randint(0, V // 2, (1,), generator=g)) + 1] = peak
+                elif kind == 2:    # a block of masked tokens
+                    lo = int(torch.randint(0, V - 600, (1,), generator=g))
+                    rows[b, n, lo:lo + 555] = float("-inf")
+                # kind 3: left as generated
+    note(request, check_case("spechub", wl, seed=31))
+
+
 # ----------------------------------------------------------------- general topology
 @pytest.mark.parametrize("method", ALL)
 def test_unbalanced_tree(method, request):
