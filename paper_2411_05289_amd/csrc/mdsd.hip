@@ -24,12 +24,12 @@ namespace mdsd {
 
 enum Method { kSpecHub = 0, kRRS = 1, kRRSw = 2 };
 
-#ifndef MDSD_QW
-#define MDSD_QW 2
-#endif
-#ifndef MDSD_STATS_WAVES
-#define MDSD_STATS_WAVES 6
-#endif
+// SpecHub verify with draft statistics: chunks of the draft row requested ahead of their use in
+// the residual pass (one is enough: a chunk pair is about 150 instructions of work for each of
+// the 6 waves that share a SIMD), and the waves per SIMD the kernel is held to (6 = 80
+// registers per lane = three workgroups per compute unit; 8 would spill).
+constexpr int kStreamAhead = 1;
+constexpr int kStatsWavesPerSimd = 6;
 
 struct Params {
     const void* target;
@@ -623,7 +623,7 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
     };
     if constexpr (STATS) {
         // the draft row's only read.  Half a chunk at a time, so that few values are live at once.
-        for_each_streamed<MDSD_QW>(sp, rq, ExpW::fill(), [&](int s, int chunk, const uint4& dp, const uint4& dq) {
+        for_each_streamed<kStreamAhead>(sp, rq, ExpW::fill(), [&](int s, int chunk, const uint4& dp, const uint4& dq) {
             constexpr int HE = E / 2;
             float part[3][2];
             auto half = [&](auto H) {
@@ -732,7 +732,7 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
 // SpecHub verify for logit rows that fit in registers: one workgroup per node, every load of the
 // node queued before anything waits, all passes from registers.
 template <int DT, int NIT, bool MASKED, bool STATS>
-__global__ __launch_bounds__(kWG, (NIT <= 8 ? (STATS ? MDSD_STATS_WAVES : 4) : 2)) void spechub_verify_resident(const Params P)
+__global__ __launch_bounds__(kWG, (NIT <= 8 ? (STATS ? kStatsWavesPerSimd : 4) : 2)) void spechub_verify_resident(const Params P)
 {
     __shared__ Shared sh;
     int phase = 0;
