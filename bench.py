@@ -141,21 +141,30 @@ def main():
     ms_per_step = 1e3 * dt / args.steps
     nodes_per_s = Bn * N * args.steps / dt
     bracket_ms = sum(e0.elapsed_time(e1) for e0, e1 in events) / args.steps
-    # What a pair of events costs by itself: the same bracket around nothing, in the same place
-    # of the step, measured after the timed region.  The kernel's duration is the bracket
-    # minus this (rocprofv3's kernel trace, which has no such overhead, is the cross-check).
-    empty = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-             for _ in range(min(args.steps, 200))]
-    for i, (e0, e1) in enumerate(empty):
-        pl = plans[i % copies]
-        pl.draft(stream)
-        e0.record()
-        e1.record()
-        pl.verify(stream)
-        pl.walk(stream)
+    # A bracket also holds what the two event markers cost (a few microseconds, as much as a
+    # tenth of this kernel).  The kernel's own duration is taken as the difference between a
+    # bracket around two launches and a bracket around one, both measured after the timed
+    # region on the rotating inputs: the markers cancel, one launch (with the gap to its
+    # neighbour) remains.  rocprofv3's kernel trace, which has no markers, is the cross-check.
+    reps = min(args.steps, 200)
+    one = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    two = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for i in range(reps):
+        a, b = plans[(2 * i) % copies], plans[(2 * i + 1) % copies]
+        a.draft(stream)
+        b.draft(stream)
+        one[i][0].record()
+        a.verify(stream)
+        one[i][1].record()
+        two[i][0].record()
+        b.verify(stream)
+        a.verify(stream)
+        two[i][1].record()
     torch.cuda.synchronize()
-    event_overhead_ms = sum(e0.elapsed_time(e1) for e0, e1 in empty) / len(empty)
-    kernel_ms = bracket_ms - event_overhead_ms
+    one_ms = sum(e0.elapsed_time(e1) for e0, e1 in one) / reps
+    two_ms = sum(e0.elapsed_time(e1) for e0, e1 in two) / reps
+    kernel_ms = two_ms - one_ms
+    event_overhead_ms = one_ms - kernel_ms
     achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
     tps = float(ad.float().mean().item()) + 1.0
     kernel_key = "%s_verify:%s" % (args.method, wl0.name)
