@@ -69,11 +69,13 @@ extern "C" {
 #define MDSD_E_ALIGN (-6)     /* pointer not element-aligned, or target/draft rows differ modulo 16 bytes */
 #define MDSD_E_WORKSPACE (-7) /* workspace smaller than mdsd_workspace_bytes()  */
 #define MDSD_E_LAUNCH (-8)    /* the HIP runtime refused a launch               */
+#define MDSD_E_UNSUPPORTED (-9) /* an output this entry point cannot give was asked for */
 
 /* per-node outcome codes (values >= 0 are the accepted child slot) */
 #define MDSD_NONE (-1)      /* no child accepted; token drawn from the residual (a leaf: from p) */
 #define MDSD_BAD_PAIR (-2)  /* SpecHub: the two tokens are not {hub, non-hub}   */
 #define MDSD_BAD_TOKEN (-3) /* a draft token id is outside [0, V)               */
+#define MDSD_UNVISITED (-4) /* *_verify_path only: the walk never reached this node */
 
 /* per-node flag bits */
 #define MDSD_FLAG_DEGENERATE_HUB 1 /* draft mass outside the hub is 0: node handled as single-draft on the hub */
@@ -194,6 +196,27 @@ int rrs_verify(const mdsd_problem* pb, const int32_t* tokens, const float* u,
                const mdsd_result* out, void* ws, size_t ws_bytes, void* stream);
 int rrsw_verify(const mdsd_problem* pb, const int32_t* tokens, const float* u,
                 const mdsd_result* out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * spechub_verify_path / rrs_verify_path / rrsw_verify_path -- the same verification
+ * restricted to the nodes that decide what the step emits (Sec. 2: verification follows the
+ * accepted tokens down the tree and stops at the first node that accepts none; the nodes
+ * beside that path have no effect on the output).  One workgroup per tree starts at the root,
+ * verifies a node exactly as the calls above do (same arguments, same uniforms, same
+ * arithmetic, so the same outcome and token), moves to the accepted child and stops like
+ * mdsd_tree_walk.  A step then reads accept_depth + 1 target rows per tree instead of N.
+ *   out->accept_depth and out->emitted are required (they are the result);
+ *   out->outcome, out->token (required), out->flags, out->resid_mass (optional) hold the
+ *   visited nodes' values, every other node MDSD_UNVISITED / -1 / 0 / 0;
+ *   out->resid_prob must be NULL (MDSD_E_UNSUPPORTED).
+ * SpecHub uses pb->draft_stats as spechub_verify does.
+ */
+int spechub_verify_path(const mdsd_problem* pb, const int32_t* tokens, const float* u,
+                        const mdsd_result* out, void* ws, size_t ws_bytes, void* stream);
+int rrs_verify_path(const mdsd_problem* pb, const int32_t* tokens, const float* u,
+                    const mdsd_result* out, void* ws, size_t ws_bytes, void* stream);
+int rrsw_verify_path(const mdsd_problem* pb, const int32_t* tokens, const float* u,
+                     const mdsd_result* out, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * mdsd_tree_walk -- the walk alone (Sec. 2: follow accepted children from the

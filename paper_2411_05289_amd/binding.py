@@ -19,12 +19,12 @@ LIB_PATH = os.path.join(_HERE, "libmdsd.so")
 
 FP32, BF16 = 0, 1
 PROBS, LOGITS = 0, 1
-NONE, BAD_PAIR, BAD_TOKEN = -1, -2, -3
+NONE, BAD_PAIR, BAD_TOKEN, UNVISITED = -1, -2, -3, -4
 FLAG_DEGENERATE_HUB, FLAG_ZERO_RESIDUAL, FLAG_Q_EXHAUSTED, FLAG_BAD_PAIR, FLAG_BAD_TOKEN = 1, 2, 4, 8, 16
 
 EXPORTS = ("mdsd_workspace_bytes", "spechub_draft", "spechub_verify", "rrs_draft", "rrsw_draft",
-           "rrs_verify", "rrsw_verify", "mdsd_tree_walk", "mdsd_philox_uniform", "mdsd_strerror",
-           "mdsd_version")
+           "rrs_verify", "rrsw_verify", "spechub_verify_path", "rrs_verify_path", "rrsw_verify_path",
+           "mdsd_tree_walk", "mdsd_philox_uniform", "mdsd_strerror", "mdsd_version")
 
 
 class MdsdError(RuntimeError):
@@ -76,7 +76,8 @@ def lib():
         L.rrs_draft.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.rrsw_draft.argtypes = L.rrs_draft.argtypes
         vv = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
-        for f in (L.spechub_verify, L.rrs_verify, L.rrsw_verify):
+        for f in (L.spechub_verify, L.rrs_verify, L.rrsw_verify,
+                  L.spechub_verify_path, L.rrs_verify_path, L.rrsw_verify_path):
             f.argtypes = vv
             f.restype = C.c_int
         for f in (L.spechub_draft, L.rrs_draft, L.rrsw_draft):
@@ -274,6 +275,20 @@ def rrsw_verify(pb: Problem, tokens, u, out=None, **want):
     return _verify("rrsw_verify", pb, tokens, u, out, **want)
 
 
+def spechub_verify_path(pb: Problem, tokens, u, out=None, **want):
+    """Alg. 3 on the nodes the walk visits only (one workgroup per tree).  -> dict(outcome,
+    token, [resid_mass], [flags], accept_depth, emitted); unvisited nodes: UNVISITED."""
+    return _verify("spechub_verify_path", pb, tokens, u, out, **want)
+
+
+def rrs_verify_path(pb: Problem, tokens, u, out=None, **want):
+    return _verify("rrs_verify_path", pb, tokens, u, out, **want)
+
+
+def rrsw_verify_path(pb: Problem, tokens, u, out=None, **want):
+    return _verify("rrsw_verify_path", pb, tokens, u, out, **want)
+
+
 def tree_walk(pb: Problem, outcome, token, accept_depth=None, emitted=None):
     B, N, _ = pb.draft.shape
     cp = _c_problem(pb)
@@ -327,6 +342,16 @@ class StepPlan:
             self._draft = lambda st: fn(pbp, ud, tk, df, None, 0, st)
         vfn = {"spechub": L.spechub_verify, "rrs": L.rrs_verify, "rrsw": L.rrsw_verify}[method]
         self._verify = lambda st: vfn(pbp, tk, uv, resp, None, 0, st)
+        # path-only: its result structure carries the walk outputs, the walk is in the kernel
+        pres = _Result()
+        for name in ("outcome", "token", "flags", "accept_depth", "emitted"):
+            t = self.out.get(name)
+            setattr(pres, name, None if t is None else t.data_ptr())
+        self._pres = pres
+        presp = C.byref(pres)
+        pfn = {"spechub": L.spechub_verify_path, "rrs": L.rrs_verify_path,
+               "rrsw": L.rrsw_verify_path}[method]
+        self._verify_path = lambda st: pfn(pbp, tk, uv, presp, None, 0, st)
         self._walk = lambda st: L.mdsd_tree_walk(pbp, oc, tok, ad, em, st)
 
     def draft(self, stream=None):
@@ -338,6 +363,11 @@ class StepPlan:
         rc = self._verify(_stream() if stream is None else stream)
         if rc != 0:
             raise MdsdError(rc, self.method + "_verify")
+
+    def verify_path(self, stream=None):
+        rc = self._verify_path(_stream() if stream is None else stream)
+        if rc != 0:
+            raise MdsdError(rc, self.method + "_verify_path")
 
     def walk(self, stream=None):
         rc = self._walk(_stream() if stream is None else stream)

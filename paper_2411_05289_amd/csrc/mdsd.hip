@@ -45,6 +45,8 @@ struct Params {
     float* resid_mass;
     int32_t* flags;
     float* resid_prob;
+    int32_t* accept_depth;  // path-only kernels
+    int32_t* emitted;
     // draft kernels
     int32_t* tokens_out;
     int32_t* hub_out;
@@ -729,14 +731,12 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
         });
 }
 
-// SpecHub verify for logit rows that fit in registers: one workgroup per node, every load of the
-// node queued before anything waits, all passes from registers.
+// One node of SpecHub verify for logit rows that fit in registers: every load of the node queued
+// before anything waits, all passes over the target row from registers.  Writes the node's
+// outputs and returns its outcome and token (the same values in every lane).
 template <int DT, int NIT, bool MASKED, bool STATS>
-__global__ __launch_bounds__(kWG, (NIT <= 8 ? (STATS ? kStatsWavesPerSimd : 4) : 2)) void spechub_verify_resident(const Params P)
+__device__ __forceinline__ NodeOut spechub_node_resident(const Params& P, const NodeId& id, Shared& sh, int& phase)
 {
-    __shared__ Shared sh;
-    int phase = 0;
-    const NodeId id = node_of_block(P);
     const bool need_full = (P.resid_mass != nullptr) || (P.resid_prob != nullptr);
     float* rprob = P.resid_prob ? P.resid_prob + id.row * (int64_t)P.V : nullptr;
     const RowView rp = make_row<DT>(P.target, P.ld_t, id.row, P.V);
@@ -760,20 +760,82 @@ __global__ __launch_bounds__(kWG, (NIT <= 8 ? (STATS ? kStatsWavesPerSimd : 4) :
         if (P.resid_mass) P.resid_mass[id.row] = o.rmass;
         if (P.flags) P.flags[id.row] = o.flags;
     }
+    return o;
+}
+
+// one workgroup per node
+template <int DT, int NIT, bool MASKED, bool STATS>
+__global__ __launch_bounds__(kWG, (NIT <= 8 ? (STATS ? kStatsWavesPerSimd : 4) : 2)) void spechub_verify_resident(const Params P)
+{
+    __shared__ Shared sh;
+    int phase = 0;
+    spechub_node_resident<DT, NIT, MASKED, STATS>(P, node_of_block(P), sh, phase);
+}
+
+// Path-only verification (Sec. 2: only the nodes the walk visits decide what a step emits): one
+// workgroup per tree starts at the root, verifies a node, and moves to the accepted child until
+// a node accepts nothing, a leaf has given its bonus token, or `depth` tokens are out.  Nodes
+// off the path keep outcome MDSD_UNVISITED.  verify_node(id) handles one node and returns its
+// outcome and token, uniform over the workgroup.
+template <class VerifyNode>
+__device__ __forceinline__ void walk_and_verify(const Params& P, VerifyNode verify_node)
+{
+    const int b = blockIdx.x;
+    for (int i = threadIdx.x; i < P.N; i += kWG) {
+        const int64_t r = (int64_t)b * P.N + i;
+        P.outcome[r] = MDSD_UNVISITED;
+        P.token[r] = -1;
+        if (P.flags) P.flags[r] = 0;
+        if (P.resid_mass) P.resid_mass[r] = 0.f;
+    }
+    int32_t* em = P.emitted + (int64_t)b * P.depth;
+    for (int i = threadIdx.x; i < P.depth; i += kWG) em[i] = -1;
+    // the visited nodes' entries are rewritten below by another thread of this workgroup
+    __threadfence_block();
+    __syncthreads();
+    int n = 0, d = 0;
+    for (;;) {
+        NodeId id;
+        id.b = b;
+        id.n = n;
+        if (P.first_child) {
+            id.c0 = P.first_child[n];
+            if (id.c0 < 1 || id.c0 + P.k > P.N) id.c0 = -1;
+        } else {
+            const int64_t c = (int64_t)P.k * n + 1;
+            id.c0 = (c + P.k <= P.N) ? (int)c : -1;
+        }
+        id.row = (int64_t)b * P.N + n;
+        const NodeOut o = verify_node(id);
+        const int outcome = uniform(o.outcome), token = uniform(o.token);
+        if (threadIdx.x == 0 && d < P.depth) em[d] = token;
+        if (id.c0 < 0 || outcome < 0 || outcome >= P.k || d + 1 >= P.depth) break;
+        n = id.c0 + outcome;
+        ++d;
+        __syncthreads();  // the next node reuses the LDS areas of this one
+    }
+    if (threadIdx.x == 0) P.accept_depth[b] = d;
+}
+
+template <int DT, int NIT, bool MASKED, bool STATS>
+__global__ __launch_bounds__(kWG, (NIT <= 8 ? 4 : 2)) void spechub_path_resident(const Params P)
+{
+    __shared__ Shared sh;
+    int phase = 0;
+    walk_and_verify(P, [&](const NodeId& id) {
+        return spechub_node_resident<DT, NIT, MASKED, STATS>(P, id, sh, phase);
+    });
 }
 
 // ---------------------------------------------------------------- verify kernel
 // Two workgroups per CU need 4 waves per SIMD, i.e. at most 128 VGPRs; the 16-chunk variant
 // holds 128 VGPRs of row data alone and runs one workgroup per CU.
 template <int DT, bool LOGITS, int METHOD, int NIT>
-__global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
+__device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id, Shared& sh, int& phase)
 {
     constexpr int E = Elem<DT>::kPerChunk;
     using CV = ToWeight<LOGITS>;
     using Src = RowSrc<DT, NIT>;
-    __shared__ Shared sh;
-    int phase = 0;
-    const NodeId id = node_of_block(P);
     const int k = P.k;
     const float* ur = P.u + id.row * (k + 1);
     const bool need_full = (P.resid_mass != nullptr) || (P.resid_prob != nullptr);
@@ -1129,6 +1191,23 @@ __global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
         if (P.resid_mass) P.resid_mass[id.row] = rmass;
         if (P.flags) P.flags[id.row] = flags;
     }
+    return NodeOut{outcome, token, flags, rmass};
+}
+
+template <int DT, bool LOGITS, int METHOD, int NIT>
+__global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
+{
+    __shared__ Shared sh;
+    int phase = 0;
+    verify_node<DT, LOGITS, METHOD, NIT>(P, node_of_block(P), sh, phase);
+}
+
+template <int DT, bool LOGITS, int METHOD, int NIT>
+__global__ __launch_bounds__(kWG) void verify_path_kernel(const Params P)
+{
+    __shared__ Shared sh;
+    int phase = 0;
+    walk_and_verify(P, [&](const NodeId& id) { return verify_node<DT, LOGITS, METHOD, NIT>(P, id, sh, phase); });
 }
 
 // ---------------------------------------------------------------- draft kernel
@@ -1420,8 +1499,17 @@ static int resident_chunks(const mdsd_problem* pb)
 }
 
 template <int DT, bool LG, int METHOD>
-static void launch_verify_n(int nit, dim3 grid, dim3 block, hipStream_t st, const Params& P)
+static void launch_verify_n(int nit, bool path, dim3 grid, dim3 block, hipStream_t st, const Params& P)
 {
+    if (path) {
+        // a tree's nodes follow one another: the row is streamed whatever its size would allow,
+        // except for the common 8-chunk case
+        if (nit == 8)
+            hipLaunchKernelGGL((verify_path_kernel<DT, LG, METHOD, 8>), grid, block, 0, st, P);
+        else
+            hipLaunchKernelGGL((verify_path_kernel<DT, LG, METHOD, 0>), grid, block, 0, st, P);
+        return;
+    }
     switch (nit) {
     case 4: hipLaunchKernelGGL((verify_kernel<DT, LG, METHOD, 4>), grid, block, 0, st, P); break;
     case 8: hipLaunchKernelGGL((verify_kernel<DT, LG, METHOD, 8>), grid, block, 0, st, P); break;
@@ -1431,13 +1519,20 @@ static void launch_verify_n(int nit, dim3 grid, dim3 block, hipStream_t st, cons
 }
 
 template <int DT>
-static void launch_spechub_resident(int nit, bool masked, dim3 grid, dim3 block, hipStream_t st, const Params& P)
+static void launch_spechub_resident(int nit, bool masked, bool path, dim3 grid, dim3 block, hipStream_t st,
+                                    const Params& P)
 {
-#define MDSD_LAUNCH_RES2(N, M)                                                                      \
+#define MDSD_LAUNCH_RES3(KERNEL, N, M)                                                              \
     if (P.stats_in)                                                                                 \
-        hipLaunchKernelGGL((spechub_verify_resident<DT, N, M, true>), grid, block, 0, st, P);       \
+        hipLaunchKernelGGL((KERNEL<DT, N, M, true>), grid, block, 0, st, P);                        \
     else                                                                                            \
-        hipLaunchKernelGGL((spechub_verify_resident<DT, N, M, false>), grid, block, 0, st, P)
+        hipLaunchKernelGGL((KERNEL<DT, N, M, false>), grid, block, 0, st, P)
+#define MDSD_LAUNCH_RES2(N, M)                                                                      \
+    if (path) {                                                                                     \
+        MDSD_LAUNCH_RES3(spechub_path_resident, N, M);                                              \
+    } else {                                                                                        \
+        MDSD_LAUNCH_RES3(spechub_verify_resident, N, M);                                            \
+    }
 #define MDSD_LAUNCH_RES(N)                                                                          \
     if (masked) {                                                                                   \
         MDSD_LAUNCH_RES2(N, true);                                                                  \
@@ -1451,8 +1546,9 @@ static void launch_spechub_resident(int nit, bool masked, dim3 grid, dim3 block,
     } else {
         MDSD_LAUNCH_RES(16);
     }
-#undef MDSD_LAUNCH_RES2
 #undef MDSD_LAUNCH_RES
+#undef MDSD_LAUNCH_RES2
+#undef MDSD_LAUNCH_RES3
 }
 
 // true when some element of some row may need masking: a row that does not start on a
@@ -1464,30 +1560,31 @@ static bool rows_need_mask(const mdsd_problem* pb)
     return (at & 15) || (ad & 15) || ((pb->ld_t * es) & 15) || ((pb->ld_d * es) & 15) || (pb->V % (16 / es));
 }
 
+// path == false: one workgroup per node.  path == true: one workgroup per tree.
 template <int METHOD>
-static void launch_verify(const mdsd_problem* pb, const Params& P, hipStream_t st)
+static void launch_verify(const mdsd_problem* pb, const Params& P, bool path, hipStream_t st)
 {
-    const dim3 grid((unsigned)(P.B * P.N)), block(kWG);
+    const dim3 grid((unsigned)(path ? P.B : P.B * P.N)), block(kWG);
     const bool lg = pb->kind == MDSD_LOGITS;
     int nit = resident_chunks(pb);
     if (METHOD == kSpecHub && lg && nit > 0) {
         if (pb->dtype == MDSD_FP32)
-            launch_spechub_resident<0>(nit, rows_need_mask(pb), grid, block, st, P);
+            launch_spechub_resident<0>(nit, rows_need_mask(pb), path, grid, block, st, P);
         else
-            launch_spechub_resident<1>(nit, rows_need_mask(pb), grid, block, st, P);
+            launch_spechub_resident<1>(nit, rows_need_mask(pb), path, grid, block, st, P);
         return;
     }
     if (METHOD != kSpecHub && nit == 16) nit = 0;  // the RRS rounds would spill with 128 registers of row data
     if (pb->dtype == MDSD_FP32) {
         if (lg)
-            launch_verify_n<0, true, METHOD>(nit, grid, block, st, P);
+            launch_verify_n<0, true, METHOD>(nit, path, grid, block, st, P);
         else
-            launch_verify_n<0, false, METHOD>(nit, grid, block, st, P);
+            launch_verify_n<0, false, METHOD>(nit, path, grid, block, st, P);
     } else {
         if (lg)
-            launch_verify_n<1, true, METHOD>(nit, grid, block, st, P);
+            launch_verify_n<1, true, METHOD>(nit, path, grid, block, st, P);
         else
-            launch_verify_n<1, false, METHOD>(nit, grid, block, st, P);
+            launch_verify_n<1, false, METHOD>(nit, path, grid, block, st, P);
     }
 }
 
@@ -1532,13 +1629,17 @@ static int walk(const mdsd_problem* pb, const int32_t* outcome, const int32_t* t
 }
 
 static int verify_entry(int method, const mdsd_problem* pb, const int32_t* tokens, const float* u,
-                        const mdsd_result* out, void* stream)
+                        const mdsd_result* out, bool path, void* stream)
 {
     Params P = {};
     const int rc = validate(pb, method, true, &P);
     if (rc != MDSD_OK) return rc;
     if (!tokens || !u || !out || !out->outcome || !out->token) return MDSD_E_NULL;
     if ((out->accept_depth == nullptr) != (out->emitted == nullptr)) return MDSD_E_NULL;
+    if (path && !out->accept_depth) return MDSD_E_NULL;
+    if (path && out->resid_prob) return MDSD_E_UNSUPPORTED;
+    P.accept_depth = out->accept_depth;
+    P.emitted = out->emitted;
     P.tokens = tokens;
     P.u = u;
     P.outcome = out->outcome;
@@ -1550,12 +1651,13 @@ static int verify_entry(int method, const mdsd_problem* pb, const int32_t* token
     hipStream_t st = (hipStream_t)stream;
     (void)hipGetLastError();
     if (method == kSpecHub)
-        launch_verify<kSpecHub>(pb, P, st);
+        launch_verify<kSpecHub>(pb, P, path, st);
     else if (method == kRRS)
-        launch_verify<kRRS>(pb, P, st);
+        launch_verify<kRRS>(pb, P, path, st);
     else
-        launch_verify<kRRSw>(pb, P, st);
+        launch_verify<kRRSw>(pb, P, path, st);
     if (hipGetLastError() != hipSuccess) return MDSD_E_LAUNCH;
+    if (path) return MDSD_OK;  // the walk is part of the kernel
     if (out->accept_depth) return walk(pb, out->outcome, out->token, out->accept_depth, out->emitted, st);
     return MDSD_OK;
 }
@@ -1623,7 +1725,7 @@ int spechub_verify(const mdsd_problem* pb, const int32_t* tokens, const float* u
 {
     (void)ws;
     (void)ws_bytes;
-    return mdsd::verify_entry(mdsd::kSpecHub, pb, tokens, u, out, stream);
+    return mdsd::verify_entry(mdsd::kSpecHub, pb, tokens, u, out, false, stream);
 }
 
 int rrs_verify(const mdsd_problem* pb, const int32_t* tokens, const float* u, const mdsd_result* out,
@@ -1631,7 +1733,7 @@ int rrs_verify(const mdsd_problem* pb, const int32_t* tokens, const float* u, co
 {
     (void)ws;
     (void)ws_bytes;
-    return mdsd::verify_entry(mdsd::kRRS, pb, tokens, u, out, stream);
+    return mdsd::verify_entry(mdsd::kRRS, pb, tokens, u, out, false, stream);
 }
 
 int rrsw_verify(const mdsd_problem* pb, const int32_t* tokens, const float* u, const mdsd_result* out,
@@ -1639,7 +1741,31 @@ int rrsw_verify(const mdsd_problem* pb, const int32_t* tokens, const float* u, c
 {
     (void)ws;
     (void)ws_bytes;
-    return mdsd::verify_entry(mdsd::kRRSw, pb, tokens, u, out, stream);
+    return mdsd::verify_entry(mdsd::kRRSw, pb, tokens, u, out, false, stream);
+}
+
+int spechub_verify_path(const mdsd_problem* pb, const int32_t* tokens, const float* u, const mdsd_result* out,
+                        void* ws, size_t ws_bytes, void* stream)
+{
+    (void)ws;
+    (void)ws_bytes;
+    return mdsd::verify_entry(mdsd::kSpecHub, pb, tokens, u, out, true, stream);
+}
+
+int rrs_verify_path(const mdsd_problem* pb, const int32_t* tokens, const float* u, const mdsd_result* out,
+                    void* ws, size_t ws_bytes, void* stream)
+{
+    (void)ws;
+    (void)ws_bytes;
+    return mdsd::verify_entry(mdsd::kRRS, pb, tokens, u, out, true, stream);
+}
+
+int rrsw_verify_path(const mdsd_problem* pb, const int32_t* tokens, const float* u, const mdsd_result* out,
+                     void* ws, size_t ws_bytes, void* stream)
+{
+    (void)ws;
+    (void)ws_bytes;
+    return mdsd::verify_entry(mdsd::kRRSw, pb, tokens, u, out, true, stream);
 }
 
 int mdsd_tree_walk(const mdsd_problem* pb, const int32_t* outcome, const int32_t* token,
@@ -1681,10 +1807,11 @@ const char* mdsd_strerror(int code)
     case MDSD_E_ALIGN: return "pointer not element-aligned, or target/draft rows differ modulo 16 bytes";
     case MDSD_E_WORKSPACE: return "workspace too small";
     case MDSD_E_LAUNCH: return "HIP launch failed";
+    case MDSD_E_UNSUPPORTED: return "output not available from this entry point";
     default: return "unknown status";
     }
 }
 
-int mdsd_version(void) { return 100; }
+int mdsd_version(void) { return 101; }
 
 }  // extern "C"

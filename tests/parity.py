@@ -21,6 +21,7 @@ RESID_MASS_ATOL = 5e-7
 METHODS = {"spechub": oracle.SPECHUB, "rrs": oracle.RRS, "rrsw": oracle.RRSW}
 DRAFT = {"spechub": B.spechub_draft, "rrs": B.rrs_draft, "rrsw": B.rrsw_draft}
 VERIFY = {"spechub": B.spechub_verify, "rrs": B.rrs_verify, "rrsw": B.rrsw_verify}
+VERIFY_PATH = {"spechub": B.spechub_verify_path, "rrs": B.rrs_verify_path, "rrsw": B.rrsw_verify_path}
 
 
 def _np(t):
@@ -114,6 +115,10 @@ def check_case(method: str, wl: Workload, seed: int = 0, seqs=None, full_outputs
             bad = (diff > tol) & ok_nodes[:, :, None]
             assert not bad.any(), "resid_prob off at %s (diff %g)" % (np.argwhere(bad)[:5], diff[bad].max())
             out["resid_prob_max_abs"] = float(diff[ok_nodes].max(initial=0.0))
+    # ---- path-only verification: the walk's outputs, and the visited nodes, against the oracle
+    g_path = VERIFY_PATH[method](pb, tokens, u_v, resid_mass=False, flags=True, walk=True)
+    out["path_nodes_visited"] = _compare_path(wl, g_path, o_v, idx, near, "path")
+
     if method == "spechub":
         # ---- the same two stages with the draft call's row statistics handed to verify
         pb_s = pb.with_draft_stats()
@@ -124,6 +129,8 @@ def check_case(method: str, wl: Workload, seed: int = 0, seqs=None, full_outputs
         out["mismatch_in_band_stats"] = _compare_nodes(g_s, o_v, idx, near, "early-exit+stats", ctx)
         _compare_walk(wl, g_s, o_v, idx, near)
         assert out["mismatch_in_band_stats"] <= 2 + 0.02 * near.size, out
+        g_path_s = VERIFY_PATH[method](pb_s, tokens, u_v, resid_mass=False, flags=True, walk=True)
+        _compare_path(wl, g_path_s, o_v, idx, near, "path+stats")
         if full_outputs:
             g_sf = VERIFY[method](pb_s, tokens, u_v, resid_mass=True, flags=True, walk=True)
             _compare_nodes(g_sf, o_v, idx, near, "full+stats", ctx)
@@ -222,6 +229,21 @@ def _compare_nodes(g, o, idx, near, label, ctx=None):
             dist = max(c[x] - w[x] - t, t - c[x], 0.0)
             assert dist <= 2 * BAND * W, "%s: token at %s is %g W away from the draw" % (label, (b, n), dist / W)
     return int(differ.sum())
+
+
+def _compare_path(wl, g, o, idx, near, label):
+    """Path-only call: walk outputs as for the full call; exactly accept_depth + 1 nodes per tree
+    visited, those equal to the oracle's outside the band, all others marked unvisited."""
+    _compare_walk(wl, g, o, idx, near)
+    oc_g, tk_g = _np(g["outcome"][idx]), _np(g["token"][idx])
+    fl_g, ad_g = _np(g["flags"][idx]), _np(g["accept_depth"][idx])
+    visited = oc_g != B.UNVISITED
+    assert (visited.sum(axis=1) == ad_g + 1).all(), "%s: visited nodes != accept depth + 1" % label
+    assert visited[:, 0].all(), "%s: root not visited" % label
+    assert (tk_g[~visited] == -1).all() and (fl_g[~visited] == 0).all()
+    differ = visited & ((oc_g != o["outcome"]) | (tk_g != o["token"]) | (fl_g != o["flags"]))
+    assert not (differ & ~near).any(), "%s: visited nodes differ at %s" % (label, np.argwhere(differ & ~near)[:5])
+    return int(visited.sum())
 
 
 def _compare_walk(wl, g, o, idx, near):
