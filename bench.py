@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--no-stats", action="store_true",
                     help="spechub_verify recomputes the draft row's hub and normalisers instead of "
                          "taking them from spechub_draft")
+    ap.add_argument("--no-path-only", action="store_true",
+                    help="skip the extra measurement of the path-only step (draft + *_verify_path)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 512 MiB device copy three times (reference dispatch for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -188,6 +190,27 @@ def main():
                      "traffic": traffic,
                      "hbm_measured_gbs": None if traffic is None else traffic / (kernel_ms * 1e-3) / 1e9},
     }
+    if not args.no_path_only:
+        # the same step with verification restricted to the nodes the walk visits (the walk is
+        # inside that kernel); reported beside the headline, never as it
+        psteps = min(args.steps, 200)
+        for i in range(min(args.warmup, 10)):
+            plans[i % copies].draft(stream)
+            plans[i % copies].verify_path(stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(psteps):
+            pl = plans[i % copies]
+            pl.draft(stream)
+            pl.verify_path(stream)
+        torch.cuda.synchronize()
+        pdt = time.perf_counter() - t0
+        visited = int((plans[(psteps - 1) % copies].out["outcome"] != B.UNVISITED).sum().item())
+        out["path_only"] = {"step": "draft+verify_path", "steps": psteps, "ms_per_step": 1e3 * pdt / psteps,
+                            "trees_per_s": Bn * psteps / pdt,
+                            "visited_nodes_per_s": visited * psteps / pdt,
+                            "visited_nodes_last_batch": visited,
+                            "full_step_trees_per_s": Bn * args.steps / dt}
     if not args.no_cpu_baseline:
         threads = min(16, os.cpu_count() or 1)
         sample_B = min(Bn, max(1, (64 * 32000) // wl0.V))     # about 2000 config-3-sized node rows

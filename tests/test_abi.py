@@ -83,6 +83,23 @@ def test_rrs_accepts_k_up_to_8_and_rejects_9():
     assert L.rrsw_verify(C.byref(p), C.c_void_p(0x5000), C.c_void_p(0x6000), C.byref(res), None, 0, None) == -2
 
 
+@pytest.mark.parametrize("name", ["spechub_verify_path", "rrs_verify_path", "rrsw_verify_path"])
+def test_path_calls_need_the_walk_outputs_and_refuse_resid_prob(name):
+    fn = getattr(B.lib(), name)
+    p = _problem()
+    args = (C.byref(p), C.c_void_p(0x5000), C.c_void_p(0x6000))
+    res = B._Result()
+    res.outcome, res.token = 0x3000, 0x4000
+    assert fn(*args, C.byref(res), None, 0, None) == -1            # accept_depth / emitted missing
+    res.accept_depth, res.emitted = 0x7000, 0x8000
+    res.resid_prob = 0x9000
+    assert fn(*args, C.byref(res), None, 0, None) == -9            # no residual rows from the path call
+    assert "not available" in B.strerror(-9)
+    bad = _problem(V=1)
+    res.resid_prob = None
+    assert fn(C.byref(bad), C.c_void_p(0x5000), C.c_void_p(0x6000), C.byref(res), None, 0, None) == -2
+
+
 def test_workspace_is_zero():
     p = _problem()
     assert B.lib().mdsd_workspace_bytes(C.byref(p)) == 0
