@@ -1211,7 +1211,7 @@ __global__ __launch_bounds__(kWG) void verify_path_kernel(const Params P)
 }
 
 // ---------------------------------------------------------------- draft kernel
-template <int DT, bool LOGITS, int METHOD, int NIT>
+template <int DT, bool LOGITS, int METHOD, int NIT, bool MASKED = true>
 __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
 {
     constexpr int E = Elem<DT>::kPerChunk;
@@ -1234,7 +1234,7 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
     const int k = P.k;
     const float* ur = P.u + row * k;
     const RowView rq = make_row<DT>(P.draft, P.ld_d, row, P.V);
-    RowSrc<DT, NIT> sq;
+    RowSrc<DT, NIT, MASKED> sq;
     sq.init(rq, CV::fill());
     int32_t* xt = P.tokens_out + (int64_t)b * P.N + c0;
     int flags = 0;
@@ -1589,8 +1589,18 @@ static void launch_verify(const mdsd_problem* pb, const Params& P, bool path, hi
 }
 
 template <int DT, bool LG, int METHOD>
-static void launch_draft_n(int nit, dim3 grid, dim3 block, hipStream_t st, const Params& P)
+static void launch_draft_n(int nit, bool masked, dim3 grid, dim3 block, hipStream_t st, const Params& P)
 {
+    // rows that need no masking of their first and last chunk: a variant without the checks,
+    // for the two common register sizes
+    if (!masked && nit == 4) {
+        hipLaunchKernelGGL((draft_kernel<DT, LG, METHOD, 4, false>), grid, block, 0, st, P);
+        return;
+    }
+    if (!masked && nit == 8) {
+        hipLaunchKernelGGL((draft_kernel<DT, LG, METHOD, 8, false>), grid, block, 0, st, P);
+        return;
+    }
     switch (nit) {
     case 4: hipLaunchKernelGGL((draft_kernel<DT, LG, METHOD, 4>), grid, block, 0, st, P); break;
     case 8: hipLaunchKernelGGL((draft_kernel<DT, LG, METHOD, 8>), grid, block, 0, st, P); break;
@@ -1605,16 +1615,18 @@ static void launch_draft(const mdsd_problem* pb, const Params& P, hipStream_t st
     const dim3 grid((unsigned)(P.B * P.N)), block(kWG);
     const bool lg = pb->kind == MDSD_LOGITS;
     const int nit = resident_chunks(pb);
+    const int es = pb->dtype == MDSD_FP32 ? 4 : 2;
+    const bool masked = ((uintptr_t)pb->draft & 15) || ((pb->ld_d * es) & 15) || (pb->V % (16 / es));
     if (pb->dtype == MDSD_FP32) {
         if (lg)
-            launch_draft_n<0, true, METHOD>(nit, grid, block, st, P);
+            launch_draft_n<0, true, METHOD>(nit, masked, grid, block, st, P);
         else
-            launch_draft_n<0, false, METHOD>(nit, grid, block, st, P);
+            launch_draft_n<0, false, METHOD>(nit, masked, grid, block, st, P);
     } else {
         if (lg)
-            launch_draft_n<1, true, METHOD>(nit, grid, block, st, P);
+            launch_draft_n<1, true, METHOD>(nit, masked, grid, block, st, P);
         else
-            launch_draft_n<1, false, METHOD>(nit, grid, block, st, P);
+            launch_draft_n<1, false, METHOD>(nit, masked, grid, block, st, P);
     }
 }
 
