@@ -119,6 +119,24 @@ def dirichlet_rows(B, N, V, *, alpha=0.3, mix=0.7, seed=0, device="cpu"):
             torch.from_numpy(q.astype(np.float32)).to(device))
 
 
+def toy_pairs(T: float, lam: float, pairs: int, *, repeats: int = 1, seed: int = 0, device="cpu") -> "Workload":
+    """The toy experiment of App. D as a batch: V = 50, one draft step (a root with its two
+    children), logits u_p, u_q ~ N(0,1) per pair, target = softmax(u_p / T), draft =
+    softmax((lam u_p + (1 - lam) u_q) / T).  (The appendix prints uniform logits; the
+    table it reports is reproduced with normal ones.)  Every pair is repeated `repeats` times
+    in a row, so that different uniforms meet the same distributions."""
+    V, k, depth = 50, 2, 2
+    N = tree_nodes(k, depth)
+    gen = torch.Generator().manual_seed(seed)
+    up = torch.randn((pairs, 1, V), generator=gen, dtype=torch.float32)
+    uq = torch.randn((pairs, 1, V), generator=gen, dtype=torch.float32)
+    t = up.expand(pairs, N, V).repeat_interleave(repeats, dim=0).contiguous()
+    d = (lam * up + (1.0 - lam) * uq).expand(pairs, N, V).repeat_interleave(repeats, dim=0).contiguous()
+    return Workload("toy_V50_T%g_lam%g" % (T, lam), pairs * repeats, N, V, k, depth, "fp32", "logits",
+                    float(T), float(T), t.to(device), d.to(device), seed,
+                    notes={"pairs": pairs, "repeats": repeats})
+
+
 CONFIG_NAMES = {
     1: "tiny_V16_k2_4096rows_probs_fp32",
     2: "V32000_B1_bin_d4_fp32_logits",
