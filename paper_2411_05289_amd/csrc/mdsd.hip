@@ -827,6 +827,60 @@ __global__ __launch_bounds__(kWG, (NIT <= 8 ? 4 : 2)) void spechub_path_resident
     });
 }
 
+// One sweep over a logit row that is streamed from memory (too long for registers), instead of
+// a pass for the maximum and a pass for the weights.  Each wave forms its weights against a
+// reference of its own, the largest element of its first slab; when the row's maximum M is
+// known the partial sums are brought to the row's units by one factor per wave,
+// 2^((reference - M) s) <= 1.  Returns false (caller falls back to two passes) when the sum
+// came out zero or not finite: some later element lay too far above a wave's reference.
+// On success: M = maximum of the stored row, Z = sum of 2^((l - M) s); with SLABS the slab
+// sums in LDS are in the same units and visible to every wave.
+template <int DT, bool SLABS, class Src>
+__device__ __forceinline__ bool sweep_streamed_row(const Src& src, float s, Shared& sh, int& phase, float& M,
+                                                   float& Z)
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    const int lane = threadIdx.x & 63, wave = wave_id();
+    const float ninf = -__builtin_inff();
+    float a0[E];
+    load_chunk<DT>(src.r, wave * 64 + lane, ninf, a0);  // slabs past the row read as -inf
+    float r = a0[0];
+#pragma unroll
+    for (int e = 1; e < E; ++e) r = fmaxf(r, a0[e]);
+    r = wave_max(r);
+    if (!(r > ninf) || !(r < __builtin_inff())) r = 0.f;  // nothing finite to refer to
+    ToWeight<true> cw;
+    cw.s = s;
+    cw.ms = uniform(r * s);
+    float lane_m = ninf, lane_z = 0.f;
+    src.for_each([&](int sl, int, const float(&a)[E]) {
+        float w[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            lane_m = fmaxf(lane_m, a[e]);
+            w[e] = cw(a[e]);
+        }
+        const float cs = chunk_sum<E>(w);
+        lane_z += cs;
+        if constexpr (SLABS) store_slab_sum(sh.slab_w, sl, cs);
+    });
+    float mm[1] = {lane_m};
+    block_max<kWaves, 1>(mm, sh.red, phase);
+    M = mm[0];
+    const float scale = uniform(__builtin_amdgcn_exp2f(fmaf(r, s, -(M * s))));
+    float zz[1] = {lane_z * scale};
+    block_sum<kWaves, 1>(zz, sh.red, phase);  // barrier: every slab sum is stored
+    Z = zz[0];
+    const bool ok = Z > 0.f && Z < __builtin_inff();
+    if constexpr (SLABS) {
+        if (ok) {
+            for (int i = wave + kWaves * lane; i < src.r.nslab; i += kWaves * 64) sh.slab_w[i] *= scale;
+        }
+        __syncthreads();
+    }
+    return ok;
+}
+
 // ---------------------------------------------------------------- verify kernel
 // Two workgroups per CU need 4 waves per SIMD, i.e. at most 128 VGPRs; the 16-chunk variant
 // holds 128 VGPRs of row data alone and runs one workgroup per CU.
@@ -851,14 +905,23 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
     if (id.c0 < 0) {
         // ---- leaf: the k = 0 case of Alg. 1, token ~ p
         CV cp{0.f, 0.f};
-        if constexpr (LOGITS) {
-            float mm[1] = {lane_max(sp)};
-            block_max<kWaves, 1>(mm, sh.red, phase);
+        bool swept = false;
+        if constexpr (LOGITS && NIT == 0) {
+            float M, Z;
             cp.s = kLog2e / P.temp_target;
-            cp.ms = mm[0] * cp.s;
+            swept = sweep_streamed_row<DT, true>(sp, cp.s, sh, phase, M, Z);
+            cp.ms = M * cp.s;
         }
-        pass_weights_to_slabs<CV>(sp, cp, nullptr, 0, sh.slab_w);
-        __syncthreads();
+        if (!swept) {
+            if constexpr (LOGITS) {
+                float mm[1] = {lane_max(sp)};
+                block_max<kWaves, 1>(mm, sh.red, phase);
+                cp.s = kLog2e / P.temp_target;
+                cp.ms = mm[0] * cp.s;
+            }
+            pass_weights_to_slabs<CV>(sp, cp, nullptr, 0, sh.slab_w);
+            __syncthreads();
+        }
         float W;
         const int v = draw_from_row<DT, CV>(rp, cp, nullptr, 0, sh.slab_w, ur[k], W);
         token = v < 0 ? -1 : v - rp.head;
@@ -876,11 +939,38 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
         CV cp{0.f, 0.f}, cq{0.f, 0.f};
 
         if constexpr (METHOD == kSpecHub) {
-            // ---- hub (argmax of the stored draft row) and softmax maxima
-            const float mq_lane = lane_max(sq);
-            float mm[2] = {LOGITS ? lane_max(sp) : 0.f, mq_lane};
-            block_max<kWaves, 2>(mm, sh.red, phase);
-            const int a_virt = block_argmax(sq, mq_lane, mm[1], sh, phase);
+            // ---- hub (argmax of the stored draft row), softmax maxima, normalisers: Zp (logits
+            // only) and the draft mass outside the hub, Zq' = sum_{y != a} eq.  With the draft
+            // call's record of the row at hand, the draft row is not read for any of them.
+            const bool have_stats = P.stats_in != nullptr;
+            mdsd_row_stats st{0.f, 0.f, 0, 0};
+            if (have_stats) {
+                st = P.stats_in[id.row];
+                if (st.hub < 0 || st.hub >= P.V) st.hub = -1;
+            }
+            float mm[2], z[2] = {0.f, 0.f};
+            int a_virt;
+            bool swept = false;
+            if (have_stats) {
+                mm[0] = 0.f;
+                if constexpr (LOGITS && NIT == 0) {
+                    // maximum and Zp of the streamed target row in one sweep
+                    swept = sweep_streamed_row<DT, false>(sp, kLog2e / P.temp_target, sh, phase, mm[0], z[0]);
+                }
+                if (!swept) {
+                    float m1[1] = {LOGITS ? lane_max(sp) : 0.f};
+                    if constexpr (LOGITS) block_max<kWaves, 1>(m1, sh.red, phase);
+                    mm[0] = m1[0];
+                }
+                mm[1] = st.max_stored;
+                a_virt = rq.head + (st.hub < 0 ? 0 : st.hub);
+            } else {
+                const float mq_lane = lane_max(sq);
+                mm[0] = LOGITS ? lane_max(sp) : 0.f;
+                mm[1] = mq_lane;
+                block_max<kWaves, 2>(mm, sh.red, phase);
+                a_virt = block_argmax(sq, mq_lane, mm[1], sh, phase);
+            }
             const int a = a_virt - rq.head;
             if constexpr (LOGITS) {
                 cp.s = kLog2e / P.temp_target;
@@ -888,21 +978,34 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                 cq.s = kLog2e / P.temp_draft;
                 cq.ms = mm[1] * cq.s;
             }
-            // ---- normalisers: Zp (logits only) and D-part Zq' = sum_{y != a} eq
             const int a_slab = a_virt / (64 * E);
-            float z[2] = {0.f, 0.f};
-            for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
-                float wp[E], wq[E];
+            if (have_stats) {
+                if (LOGITS && !swept) {
+                    float z1[1] = {0.f};
+                    sp.for_each([&](int, int, const float(&pa_)[E]) {
+                        float wp[E];
 #pragma unroll
-                for (int e = 0; e < E; ++e) {
-                    wp[e] = cp(pa_[e]);
-                    wq[e] = cq(qa_[e]);
+                        for (int e = 0; e < E; ++e) wp[e] = cp(pa_[e]);
+                        z1[0] += chunk_sum<E>(wp);
+                    });
+                    block_sum<kWaves, 1>(z1, sh.red, phase);
+                    z[0] = z1[0];
                 }
-                if (s == a_slab) zero_excluded<E>(wq, chunk, &a_virt, 1);
-                z[0] += chunk_sum<E>(wp);
-                z[1] += chunk_sum<E>(wq);
-            });
-            block_sum<kWaves, 2>(z, sh.red, phase);
+                z[1] = st.rest_mass;
+            } else {
+                for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
+                    float wp[E], wq[E];
+#pragma unroll
+                    for (int e = 0; e < E; ++e) {
+                        wp[e] = cp(pa_[e]);
+                        wq[e] = cq(qa_[e]);
+                    }
+                    if (s == a_slab) zero_excluded<E>(wq, chunk, &a_virt, 1);
+                    z[0] += chunk_sum<E>(wp);
+                    z[1] += chunk_sum<E>(wq);
+                });
+                block_sum<kWaves, 2>(z, sh.red, phase);
+            }
             const float ea_q = cq(load_elem<DT>(rq, a));
             const float ea_p = cp(load_elem<DT>(rp, a));
             const float Zq_rest = z[1];
@@ -916,7 +1019,11 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
             const int x1 = xt[0], x2 = xt[1];
             bool decided = false, degenerate = false;
             int hub_slot = -1;  // slot of the hub token in the pair
-            if (x1 < 0 || x1 >= P.V || x2 < 0 || x2 >= P.V) {
+            if (have_stats && st.hub < 0) {  // no usable record for this node
+                flags |= MDSD_FLAG_BAD_PAIR;
+                outcome = MDSD_BAD_PAIR;
+                decided = true;
+            } else if (x1 < 0 || x1 >= P.V || x2 < 0 || x2 >= P.V) {
                 flags |= MDSD_FLAG_BAD_TOKEN;
                 outcome = MDSD_BAD_TOKEN;
                 decided = true;

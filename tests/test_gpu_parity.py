@@ -128,11 +128,13 @@ def test_temperatures(method, T, request):
     note(request, check_case(method, wl, seed=int(T * 10)))
 
 
-def test_rows_with_isolated_peaks(request):
+@pytest.mark.parametrize("V,Bn", [(4096, 6), (70016, 2)], ids=["in_registers", "streamed"])
+def test_rows_with_isolated_peaks(V, Bn, request):
     """bf16 rows whose largest logits sit far above the rest at even and at odd token indices
-    (a shift taken from every second element would overflow or underflow the weights), and
-    rows holding -inf (masked tokens): the softmax must still be the exact one."""
-    wl = W.config(3, device=DEV, B=6, V=4096, seed=31)
+    (a shift taken from part of the row would overflow or underflow the weights), and
+    rows holding -inf (masked tokens): the softmax must still be the exact one.  Once with rows
+    that stay in registers, once with rows long enough to be streamed."""
+    wl = W.config(3, device=DEV, B=Bn, V=V, seed=31)
     g = torch.Generator(device="cpu").manual_seed(31)
     # the target's peaks leave every other weight at zero in fp32; the draft's stay moderate, so
     # that its mass outside the hub does not vanish in fp32 while it is positive in fp64
