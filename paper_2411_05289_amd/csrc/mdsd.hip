@@ -837,7 +837,7 @@ __global__ __launch_bounds__(kWG, (NIT <= 8 ? 4 : 2)) void spechub_path_resident
 // sums in LDS are in the same units and visible to every wave.
 template <int DT, bool SLABS, class Src>
 __device__ __forceinline__ bool sweep_streamed_row(const Src& src, float s, Shared& sh, int& phase, float& M,
-                                                   float& Z)
+                                                   float& Z, float* lane_max_out = nullptr)
 {
     constexpr int E = Elem<DT>::kPerChunk;
     const int lane = threadIdx.x & 63, wave = wave_id();
@@ -864,6 +864,7 @@ __device__ __forceinline__ bool sweep_streamed_row(const Src& src, float s, Shar
         lane_z += cs;
         if constexpr (SLABS) store_slab_sum(sh.slab_w, sl, cs);
     });
+    if (lane_max_out) *lane_max_out = lane_m;
     float mm[1] = {lane_m};
     block_max<kWaves, 1>(mm, sh.red, phase);
     M = mm[0];
@@ -1349,17 +1350,30 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
     CV cq{0.f, 0.f};
     int a_virt = rq.head;
     float mm[1] = {0.f};
-    if (LOGITS || METHOD == kSpecHub) {
-        const float mq_lane = lane_max(sq);
-        mm[0] = mq_lane;
-        block_max<kWaves, 1>(mm, sh.red, phase);
-        if constexpr (METHOD == kSpecHub) a_virt = block_argmax(sq, mq_lane, mm[0], sh, phase);
-        if constexpr (LOGITS) {
-            cq.s = kLog2e / P.temp_draft;
+    bool swept = false;
+    if constexpr (LOGITS && NIT == 0) {
+        // a streamed logit row: maximum, weights and slab sums in one sweep
+        float Z, mq_lane;
+        cq.s = kLog2e / P.temp_draft;
+        swept = sweep_streamed_row<DT, true>(sq, cq.s, sh, phase, mm[0], Z, &mq_lane);
+        if (swept) {
             cq.ms = mm[0] * cq.s;
+            if constexpr (METHOD == kSpecHub) a_virt = block_argmax(sq, mq_lane, mm[0], sh, phase);
         }
     }
-    pass_weights_to_slabs<CV>(sq, cq, nullptr, 0, sh.slab_w);
+    if (!swept) {
+        if (LOGITS || METHOD == kSpecHub) {
+            const float mq_lane = lane_max(sq);
+            mm[0] = mq_lane;
+            block_max<kWaves, 1>(mm, sh.red, phase);
+            if constexpr (METHOD == kSpecHub) a_virt = block_argmax(sq, mq_lane, mm[0], sh, phase);
+            if constexpr (LOGITS) {
+                cq.s = kLog2e / P.temp_draft;
+                cq.ms = mm[0] * cq.s;
+            }
+        }
+        pass_weights_to_slabs<CV>(sq, cq, nullptr, 0, sh.slab_w);
+    }
     __syncthreads();
 
     // slab sums with some tokens removed: only the slabs holding a removed token change,
