@@ -165,13 +165,25 @@ __device__ __forceinline__ void pass_weights_to_slabs(const Src& src, CV cv, con
                                                       float* slab_w)
 {
     constexpr int E = Src::E;
-    src.for_each([&](int s, int chunk, const float(&a)[E]) {
-        float w[E];
+    if constexpr (Src::kNit > 0) {
+        SlabSums<Src::kNit> sums;
+        src.for_each_it([&](int it, int s, int chunk, const float(&a)[E]) {
+            float w[E];
 #pragma unroll
-        for (int e = 0; e < E; ++e) w[e] = cv(a[e]);
-        if (slab_has_excluded<E>(s, excl, n_excl)) zero_excluded<E>(w, chunk, excl, n_excl);
-        store_slab_sum(slab_w, s, chunk_sum<E>(w));
-    });
+            for (int e = 0; e < E; ++e) w[e] = cv(a[e]);
+            if (slab_has_excluded<E>(s, excl, n_excl)) zero_excluded<E>(w, chunk, excl, n_excl);
+            sums.put(it, chunk_sum<E>(w));
+        });
+        sums.store(slab_w, src.r.nslab);
+    } else {
+        src.for_each([&](int s, int chunk, const float(&a)[E]) {
+            float w[E];
+#pragma unroll
+            for (int e = 0; e < E; ++e) w[e] = cv(a[e]);
+            if (slab_has_excluded<E>(s, excl, n_excl)) zero_excluded<E>(w, chunk, excl, n_excl);
+            store_slab_sum(slab_w, s, chunk_sum<E>(w));
+        });
+    }
 }
 
 // this lane's chunk of slab s of the same weights, read from memory (the draw
@@ -625,7 +637,8 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
     };
     if constexpr (STATS) {
         // the draft row's only read.  Half a chunk at a time, so that few values are live at once.
-        for_each_streamed<kStreamAhead>(sp, rq, ExpW::fill(), [&](int s, int chunk, const uint4& dp, const uint4& dq) {
+        SlabSums<NIT> wsums;
+        for_each_streamed<kStreamAhead>(sp, rq, ExpW::fill(), [&](int it, int s, int chunk, const uint4& dp, const uint4& dq) {
             constexpr int HE = E / 2;
             float part[3][2];
             auto half = [&](auto H) {
@@ -663,8 +676,9 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
             half(std::integral_constant<int, 1>{});
             sacc[0] += part[0][0] + part[0][1];
             sacc[1] += part[1][0] + part[1][1];
-            store_slab_sum(sh.slab_w, s, part[2][0] + part[2][1]);
+            wsums.put(it, part[2][0] + part[2][1]);
         });
+        wsums.store(sh.slab_w, rp.nslab);
     } else {
         for_each2(sp, sq, residual_terms);
     }

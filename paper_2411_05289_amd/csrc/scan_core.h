@@ -62,6 +62,7 @@ __device__ __forceinline__ float chunk_sum(const float (&w)[E])
 template <int DT, int NIT, bool MASKED = true>
 struct RowSrc {
     static constexpr int E = Elem<DT>::kPerChunk;
+    static constexpr int kNit = NIT;
     RowView r;
     float fill;
     uint4 d[NIT];
@@ -118,6 +119,22 @@ struct RowSrc {
         }
     }
 
+    // body(it, slab, chunk, a[E]): as for_each, with the number of the register chunk
+    template <class Body>
+    __device__ __forceinline__ void for_each_it(Body body) const
+    {
+        const int lane = threadIdx.x & 63, wave = wave_id();
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int s = it * kWaves + wave;
+            if (s < r.nslab) {
+                float a[E];
+                get(it, a);
+                body(it, s, s * 64 + lane, a);
+            }
+        }
+    }
+
     // A softmax shift for a quarter of the work of an exact maximum.  bf16 rows that need no
     // masking only: the largest 32-bit word of this lane's chunks read as a float, which is the
     // odd-indexed element with its neighbour's bits as extra mantissa (less than one bf16 ulp
@@ -143,6 +160,7 @@ struct RowSrc {
 template <int DT, bool MASKED>
 struct RowSrc<DT, 0, MASKED> {
     static constexpr int E = Elem<DT>::kPerChunk;
+    static constexpr int kNit = 0;
     RowView r;
     float fill;
 
@@ -221,7 +239,7 @@ __device__ __forceinline__ void unpack_half(const uint4& d, const RowView& r, fl
     }
 }
 
-// body(slab, chunk, a, b) with the packed chunks of row a (in registers) and of row b, which is
+// body(it, slab, chunk, a, b) with the packed chunks of row a (register chunk it) and of row b, which is
 // read from memory as the loop goes, QW chunks ahead of their use: b is read exactly once and
 // never held whole.  Chunks of b past the end of the row read as `fill_b`.
 template <int QW, int DT, int NIT, bool MASKED, class Body>
@@ -244,7 +262,7 @@ __device__ __forceinline__ void for_each_streamed(const RowSrc<DT, NIT, MASKED>&
         const int s = it * kWaves + wave;
         const uint4 cur = win[it % QW];
         if (it + QW < NIT) win[it % QW] = fetch(it + QW);
-        if (s < sa.r.nslab) body(s, s * 64 + lane, sa.d[it], cur);
+        if (s < sa.r.nslab) body(it, s, s * 64 + lane, sa.d[it], cur);
         __builtin_amdgcn_sched_barrier(0);  // one chunk pair at a time
     }
 }
@@ -255,6 +273,32 @@ __device__ __forceinline__ void store_slab_sum(float* slab_w, int s, float lane_
     const float t = wave_scan_add(lane_sum);
     if ((threadIdx.x & 63) == 63) slab_w[s] = t;
 }
+
+// The slab sums of a row held in registers, reduced eight at a time: put() takes this lane's sum
+// of its register chunk `it` (slab it * kWaves + wave), store() leaves every slab's sum in LDS.
+template <int NIT>
+struct SlabSums {
+    static constexpr int kSlots = (NIT + 7) / 8 * 8;
+    float v[kSlots];
+    __device__ __forceinline__ SlabSums()
+    {
+#pragma unroll
+        for (int i = 0; i < kSlots; ++i) v[i] = 0.f;
+    }
+    __device__ __forceinline__ void put(int it, float lane_sum) { v[it] = lane_sum; }
+    __device__ __forceinline__ void store(float* slab_w, int nslab) const
+    {
+        const int lane = threadIdx.x & 63, wave = wave_id();
+#pragma unroll
+        for (int b = 0; b < kSlots / 8; ++b) {
+            const float g[8] = {v[8 * b], v[8 * b + 1], v[8 * b + 2], v[8 * b + 3],
+                                v[8 * b + 4], v[8 * b + 5], v[8 * b + 6], v[8 * b + 7]};
+            const float t = wave_sums8(g);
+            const int s = (8 * b + lane) * kWaves + wave;
+            if (lane < 8 && s < nslab) slab_w[s] = t;
+        }
+    }
+};
 
 // Sum of the slab sums, in slab order.  Every wave computes it on its own
 // (identical arithmetic, so identical bits) -- no broadcast needed.

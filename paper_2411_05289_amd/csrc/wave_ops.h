@@ -29,6 +29,8 @@ __device__ __forceinline__ float dpp(float old, float v)
 
 constexpr int kRowShr1 = 0x111, kRowShr2 = 0x112, kRowShr4 = 0x114, kRowShr8 = 0x118;
 constexpr int kRowBcast15 = 0x142, kRowBcast31 = 0x143, kWaveShr1 = 0x138;
+// lane i reads lane 7 - i of its group of 8; lane i ^ 1; lane i ^ 2; lane i ^ 8
+constexpr int kRowHalfMirror = 0x141, kQuadXor1 = 0xB1, kQuadXor2 = 0x4E, kRowRor8 = 0x128;
 
 // Inclusive prefix sum over the 64 lanes; lane 63 ends with the wave total.
 __device__ __forceinline__ float wave_scan_add(float v)
@@ -61,6 +63,34 @@ __device__ __forceinline__ float lane_bcast(float v, int lane)
 
 __device__ __forceinline__ float wave_sum(float v) { return lane_bcast(wave_scan_add(v), 63); }
 __device__ __forceinline__ float wave_max(float v) { return lane_bcast(wave_scan_max(v), 63); }
+
+// Eight wave-wide sums for the price of about two: every lane passes eight values; on return
+// lane l holds the sum over all 64 lanes of value number (l & 7).  Three halving steps inside
+// each group of 8 lanes (every lane keeps the half of the values that its own bit selects and
+// hands the other half to its partner), then the 8 groups are added up.  Fixed order of
+// additions: the result is the same from launch to launch.
+__device__ __forceinline__ float wave_sums8(const float (&v)[8])
+{
+    const int lane = threadIdx.x & 63;
+    const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4;
+    float k[4], m[2];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float keep = b2 ? v[4 + j] : v[j], send = b2 ? v[j] : v[4 + j];
+        k[j] = keep + dpp<kRowHalfMirror>(0.f, send);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const float keep = b0 ? k[2 * j + 1] : k[2 * j], send = b0 ? k[2 * j] : k[2 * j + 1];
+        m[j] = keep + dpp<kQuadXor1>(0.f, send);
+    }
+    const float keep = b1 ? m[1] : m[0], send = b1 ? m[0] : m[1];
+    float r = keep + dpp<kQuadXor2>(0.f, send);
+    r += dpp<kRowRor8>(0.f, r);
+    r += __shfl_xor(r, 16, 64);
+    r += __shfl_xor(r, 32, 64);
+    return r;
+}
 
 // value of the lane below (lane 0 reads `fill`)
 __device__ __forceinline__ float wave_shift_up(float v, float fill)
