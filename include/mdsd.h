@@ -92,9 +92,12 @@ extern "C" {
  * first acceptance test (Alg. 3, the non-hub token) succeeds then never reads its draft row.
  * The records must come from spechub_draft on the same draft rows, dtype, kind and
  * temp_draft: the library cannot check that.  A hub outside [0,V) makes the node
- * MDSD_BAD_PAIR.  Only the kernels for logit rows that fit in registers use the records;
- * every other path recomputes them from the rows, so results never depend on the pointer
- * beyond fp32 rounding of rest_mass (a different summation order).
+ * MDSD_BAD_PAIR.  Results depend on the pointer only through fp32 rounding of rest_mass (a
+ * different summation order).
+ * rrs_draft writes records too (hub = -1, rest_mass = the mass of the whole row) and
+ * rrs_verify reads them the same way; without replacement the normaliser depends on the drafted
+ * tokens, so rrsw_draft / rrsw_verify ignore the pointer.  Records must come from the draft
+ * call of the same method.
  */
 typedef struct mdsd_row_stats {
     float max_stored; /* largest stored element of the row (a logit, or a probability)        */

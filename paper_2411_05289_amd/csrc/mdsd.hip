@@ -949,7 +949,13 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
     } else {
         const RowView rq = make_row<DT>(P.draft, P.ld_d, id.row, P.V);
         Src sq;
-        sq.init(rq, CV::fill());
+        // the draft row is asked for when a pass first needs it: with the draft call's record of
+        // the row at hand, a node that accepts in its first test never reads it
+        bool q_asked = false;
+        auto need_q = [&]() {
+            if (!q_asked) sq.init(rq, CV::fill());
+            q_asked = true;
+        };
         const int32_t* xt = P.tokens + (int64_t)id.b * P.N + id.c0;
         CV cp{0.f, 0.f}, cq{0.f, 0.f};
 
@@ -980,6 +986,7 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                 mm[1] = st.max_stored;
                 a_virt = rq.head + (st.hub < 0 ? 0 : st.hub);
             } else {
+                need_q();
                 const float mq_lane = lane_max(sq);
                 mm[0] = LOGITS ? lane_max(sp) : 0.f;
                 mm[1] = mq_lane;
@@ -1102,6 +1109,7 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                 } else {
                     // ---- residual sums: S_xa = sum Q'(.,a), S_ax = sum Q'(a,.), slab sums of p''
                     float sacc[2] = {0.f, 0.f};
+                    need_q();
                     for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
                         float ep[E], eq[E], t_xa[E], t_ax[E], w[E];
 #pragma unroll
@@ -1179,9 +1187,32 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                 flags |= MDSD_FLAG_BAD_TOKEN;
                 outcome = MDSD_BAD_TOKEN;
             } else {
+                // With replacement the draft call's record (largest stored element, total mass)
+                // stands in for the statistics of the draft row; without replacement the
+                // normaliser depends on the drafted tokens and the row is read.
+                const bool have_stats = !WO && P.stats_in != nullptr;
+                mdsd_row_stats st{0.f, 0.f, -1, 0};
+                if (have_stats) st = P.stats_in[id.row];
+                float z[2] = {0.f, 0.f};
+                bool swept = false;
                 if constexpr (LOGITS) {
-                    float mm[2] = {lane_max(sp), lane_max(sq)};
-                    block_max<kWaves, 2>(mm, sh.red, phase);
+                    float mm[2];
+                    if (have_stats) {
+                        mm[0] = 0.f;
+                        if constexpr (NIT == 0)
+                            swept = sweep_streamed_row<DT, false>(sp, kLog2e / P.temp_target, sh, phase, mm[0], z[0]);
+                        if (!swept) {
+                            float m1[1] = {lane_max(sp)};
+                            block_max<kWaves, 1>(m1, sh.red, phase);
+                            mm[0] = m1[0];
+                        }
+                        mm[1] = st.max_stored;
+                    } else {
+                        need_q();
+                        mm[0] = lane_max(sp);
+                        mm[1] = lane_max(sq);
+                        block_max<kWaves, 2>(mm, sh.red, phase);
+                    }
                     cp.s = kLog2e / P.temp_target;
                     cp.ms = mm[0] * cp.s;
                     cq.s = kLog2e / P.temp_draft;
@@ -1197,21 +1228,36 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                 }
                 // normalisers; without replacement the draft sum leaves out every draft token,
                 // so that the mass remaining after i removals is a sum of positive terms
-                float z[2] = {0.f, 0.f};
-                for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
-                    float wp[E], wq[E];
+                if (have_stats) {
+                    if (LOGITS && !swept) {
+                        float z1[1] = {0.f};
+                        sp.for_each([&](int, int, const float(&pa_)[E]) {
+                            float wp[E];
 #pragma unroll
-                    for (int e = 0; e < E; ++e) {
-                        wp[e] = cp(pa_[e]);
-                        wq[e] = cq(qa_[e]);
+                            for (int e = 0; e < E; ++e) wp[e] = cp(pa_[e]);
+                            z1[0] += chunk_sum<E>(wp);
+                        });
+                        block_sum<kWaves, 1>(z1, sh.red, phase);
+                        z[0] = z1[0];
                     }
-                    if constexpr (WO) {
-                        if (slab_has_excluded<E>(s, xv, k)) zero_excluded<E>(wq, chunk, xv, k);
-                    }
-                    z[0] += chunk_sum<E>(wp);
-                    z[1] += chunk_sum<E>(wq);
-                });
-                block_sum<kWaves, 2>(z, sh.red, phase);
+                    z[1] = st.rest_mass;
+                } else {
+                    need_q();
+                    for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
+                        float wp[E], wq[E];
+#pragma unroll
+                        for (int e = 0; e < E; ++e) {
+                            wp[e] = cp(pa_[e]);
+                            wq[e] = cq(qa_[e]);
+                        }
+                        if constexpr (WO) {
+                            if (slab_has_excluded<E>(s, xv, k)) zero_excluded<E>(wq, chunk, xv, k);
+                        }
+                        z[0] += chunk_sum<E>(wp);
+                        z[1] += chunk_sum<E>(wq);
+                    });
+                    block_sum<kWaves, 2>(z, sh.red, phase);
+                }
                 float eqx[MDSD_MAX_K], rem[MDSD_MAX_K + 1];
                 for (int i = 0; i < k; ++i) eqx[i] = cq(load_elem<DT>(rq, xs[i]));
                 // rem[i] = draft mass (unnormalised) left before round i
@@ -1250,6 +1296,7 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                     n_rej = i + 1;
                     if (i > 0) __syncthreads();  // earlier readers of slab_w are done
                     const float c_iZq = c_new * iZq;
+                    need_q();
                     for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
                         float w[E];
 #pragma unroll
@@ -1284,6 +1331,7 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                         // the slab sums in LDS are not those of the current residual (accepted in
                         // the first round, or a round without mass): rebuild them
                         __syncthreads();
+                        need_q();
                         for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
                             float w[E];
 #pragma unroll
@@ -1477,6 +1525,8 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
         int prev = rq.head;
         for (int i = 0; i < k; ++i) {
             const float W = slab_total(rq.nslab, sv);
+            if (i == 0 && P.stats_out && threadIdx.x == 0)  // with replacement: maximum and total mass
+                P.stats_out[row] = mdsd_row_stats{mm[0], W, -1, 0};
             int v = draw(ur[i], W);
             if (v < 0) {
                 v = prev;
@@ -1794,7 +1844,7 @@ static int verify_entry(int method, const mdsd_problem* pb, const int32_t* token
     P.resid_mass = out->resid_mass;
     P.flags = out->flags;
     P.resid_prob = out->resid_prob;
-    P.stats_in = method == kSpecHub ? pb->draft_stats : nullptr;
+    P.stats_in = method != kRRSw ? pb->draft_stats : nullptr;
     hipStream_t st = (hipStream_t)stream;
     (void)hipGetLastError();
     if (method == kSpecHub)
@@ -1820,7 +1870,7 @@ static int draft_entry(int method, const mdsd_problem* pb, const float* u, int32
     P.tokens_out = tokens;
     P.hub_out = hub;
     P.flags = flags;
-    P.stats_out = method == kSpecHub ? pb->draft_stats : nullptr;
+    P.stats_out = method != kRRSw ? pb->draft_stats : nullptr;
     hipStream_t st = (hipStream_t)stream;
     (void)hipGetLastError();
     if (method == kSpecHub)

@@ -119,12 +119,14 @@ def check_case(method: str, wl: Workload, seed: int = 0, seqs=None, full_outputs
     g_path = VERIFY_PATH[method](pb, tokens, u_v, resid_mass=False, flags=True, walk=True)
     out["path_nodes_visited"] = _compare_path(wl, g_path, o_v, idx, near, "path")
 
-    if method == "spechub":
+    if method in ("spechub", "rrs"):
         # ---- the same two stages with the draft call's row statistics handed to verify
         pb_s = pb.with_draft_stats()
         g_ds = DRAFT[method](pb_s, u_d)
-        assert torch.equal(g_ds["tokens"], g_d["tokens"]) and torch.equal(g_ds["hub"], g_d["hub"])
-        _check_stats(wl, _np(pb_s.draft_stats[idx]), d_np, o_d["hub"], internal)
+        assert torch.equal(g_ds["tokens"], g_d["tokens"])
+        if method == "spechub":
+            assert torch.equal(g_ds["hub"], g_d["hub"])
+        _check_stats(wl, _np(pb_s.draft_stats[idx]), d_np, o_d["hub"] if method == "spechub" else None, internal)
         g_s = VERIFY[method](pb_s, tokens, u_v, resid_mass=False, flags=True, walk=True)
         out["mismatch_in_band_stats"] = _compare_nodes(g_s, o_v, idx, near, "early-exit+stats", ctx)
         _compare_walk(wl, g_s, o_v, idx, near)
@@ -148,20 +150,25 @@ def check_case(method: str, wl: Workload, seed: int = 0, seqs=None, full_outputs
 
 
 def _check_stats(wl: Workload, stats, d_np, hub, internal):
-    """Records left by spechub_draft: hub index, the row's largest stored element, and the
-    draft mass outside the hub (unnormalised for logits), against fp64 sums over the rows."""
+    """Records left by spechub_draft (hub index, the row's largest stored element, the draft
+    mass outside the hub) or rrs_draft (no hub, the mass of the whole row), unnormalised for
+    logits, against fp64 sums over the rows."""
     st_hub = stats[..., 2].copy().view(np.int32)
-    assert (st_hub[:, internal] == hub[:, internal]).all(), "stats hub differs"
-    assert (st_hub[:, ~internal] == -1).all()
+    if hub is None:        # RRS: no hub, the mass of the whole row
+        assert (st_hub == -1).all()
+    else:
+        assert (st_hub[:, internal] == hub[:, internal]).all(), "stats hub differs"
+        assert (st_hub[:, ~internal] == -1).all()
     rows = _to_f64(d_np, wl.dtype)[:, internal]
-    a = hub[:, internal]
     m = rows.max(axis=-1)
-    assert (stats[..., 0][:, internal].astype(np.float64) == m).all(), "stats max differs"
+    if wl.kind == "logits" or hub is not None:
+        assert (stats[..., 0][:, internal].astype(np.float64) == m).all(), "stats max differs"
     if wl.kind == "logits":
         w = np.exp((rows - m[..., None]) / np.float64(np.float32(wl.temp_draft)))
     else:
         w = rows.copy()
-    np.put_along_axis(w, a[..., None], 0.0, axis=-1)
+    if hub is not None:
+        np.put_along_axis(w, hub[:, internal][..., None], 0.0, axis=-1)
     rest = w.sum(axis=-1)
     got = stats[..., 1][:, internal].astype(np.float64)
     assert np.allclose(got, rest, rtol=1e-5, atol=1e-30), "stats rest_mass off: %g" % np.abs(got / rest - 1).max()
