@@ -243,11 +243,24 @@ __device__ __forceinline__ void unpack_half(const uint4& d, const RowView& r, fl
 // read from memory as the loop goes, QW chunks ahead of their use: b is read exactly once and
 // never held whole.  Chunks of b past the end of the row read as `fill_b`.
 template <int QW, int DT, int NIT, bool MASKED, class Body>
+__device__ __forceinline__ void for_each_streamed_at(int lane, int wave, const RowSrc<DT, NIT, MASKED>& sa,
+                                                     const RowView& rb, float fill_b, Body body);
+
+template <int QW, int DT, int NIT, bool MASKED, class Body>
 __device__ __forceinline__ void for_each_streamed(const RowSrc<DT, NIT, MASKED>& sa, const RowView& rb,
                                                   float fill_b, Body body)
 {
+    for_each_streamed_at<QW>((int)(threadIdx.x & 63), wave_id(), sa, rb, fill_b, body);
+}
+
+// the same with the lane and wave numbers handed in (a caller that runs the pass inside a loop
+// hands in copies the compiler cannot see through, so that it does not hoist the address and
+// mask arithmetic of every chunk out of that loop and hold it in registers)
+template <int QW, int DT, int NIT, bool MASKED, class Body>
+__device__ __forceinline__ void for_each_streamed_at(int lane, int wave, const RowSrc<DT, NIT, MASKED>& sa,
+                                                     const RowView& rb, float fill_b, Body body)
+{
     static_assert(NIT > 0 && QW > 0, "row a must be resident");
-    const int lane = threadIdx.x & 63, wave = wave_id();
     const uint32_t fb = __builtin_bit_cast(uint32_t, fill_b);
     const uint32_t fw = DT == 0 ? fb : ((fb >> 16) | (fb & 0xffff0000u));
     auto fetch = [&](int it) {
