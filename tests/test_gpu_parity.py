@@ -154,6 +154,20 @@ def test_rows_with_isolated_peaks(V, Bn, request):
     note(request, check_case("spechub", wl, seed=31))
 
 
+@pytest.mark.parametrize("method", ALL)
+def test_largest_supported_vocabulary(method, request):
+    """bf16 rows of 2048 slabs minus one chunk, the longest the per-slab sums in LDS allow
+    (one more chunk is refused with MDSD_E_SHAPE)."""
+    V = 2048 * 64 * 8 - 8
+    wl = W.config(3, device=DEV, B=2, V=V, depth=2, seed=41)
+    note(request, check_case(method, wl, seed=41, full_outputs=False))
+    too_long = W.config(3, device=DEV, B=1, V=V + 8, depth=2, seed=41)
+    with pytest.raises(B.MdsdError) as err:
+        B.spechub_draft(B.Problem.from_workload(too_long),
+                        torch.zeros((1, too_long.N, 2), dtype=torch.float32, device=DEV))
+    assert err.value.code == -2
+
+
 # ----------------------------------------------------------------- general topology
 @pytest.mark.parametrize("method", ALL)
 def test_unbalanced_tree(method, request):
