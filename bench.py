@@ -32,6 +32,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--config", type=int, default=3, help="workload configuration 2..5 (3 = the metric's)")
     ap.add_argument("--method", default="spechub", choices=["spechub", "rrs", "rrsw"])
+    ap.add_argument("--batch", type=int, default=0, help="trees per batch (0 = the configuration's own)")
     ap.add_argument("--copies", type=int, default=0, help="distinct input copies to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
@@ -100,6 +101,8 @@ def main():
     over = {}
     if args.config == 5 and args.method == "spechub":
         over = dict(k=2, depth=4)
+    if args.batch > 0:
+        over["B"] = args.batch
     wl0 = W.config(args.config, device=dev, seed=args.seed, **over)
     alg_bytes = wl0.algorithmic_bytes()
     copies = args.copies or max(2, -(-3 * 256 * 2 ** 20 // alg_bytes))   # >= 3x the Infinity Cache
