@@ -1,15 +1,21 @@
 // HIP kernels and C ABI of the sampling-verification library (gfx950).
 //
-// One workgroup of 256 threads owns one tree node: it scans the node's target
-// row (and, for a node with children, its draft row) a few times, each scan a
-// sequence of fully coalesced 16-byte loads, and decides the node's outcome.
-// The passes of one node:
-//   max     max of the stored logits (and the hub = argmax of the draft row)
-//   norm    softmax normalisers (sum of 2^((l - max) * log2e / T))
-//   resid   the vocabulary-wide residual sums of the method, with one partial
-//           sum per slab left in LDS
+// One workgroup of 512 threads (8 wavefronts) owns one tree node -- or, in the path-only
+// kernels, one tree, whose visited nodes it handles one after another.  A node's work is a few
+// passes over its target row and, if it has children, its draft row, each pass a sequence of
+// fully coalesced 16-byte loads or a sweep over registers that hold the row:
+//   shift   a softmax shift for the stored logits: the row maximum, or a cheap estimate of it
+//           (and the hub = argmax of the draft row, unless the draft call handed it on)
+//   norm    softmax normalisers, sum of 2^((l - shift) * log2e / T)
+//   test    scalar look-ups of p(x), q(x) at the draft tokens and the first acceptance test;
+//           most nodes end here
+//   resid   the vocabulary-wide residual sums of the method, one partial sum per slab in LDS
 //   draw    inverse-CDF search over the slab sums, then inside one slab
-// Scalar look-ups of p(x), q(x) at the draft tokens sit between them.
+// Kernel families, in the order of this file: helpers for the passes; the SpecHub kernel for
+// logit rows in registers (spechub_*_resident); the RRS kernel for the same (rrs_*_resident);
+// the one-sweep statistics of streamed rows; the generic kernel for everything else
+// (verify_node); the draft kernel; tree walk; Philox; host-side validation, dispatch and the
+// C entry points.
 #include <hip/hip_runtime.h>
 #include <type_traits>
 #include <limits.h>
