@@ -223,6 +223,42 @@ def test_invalid_tokens_and_pairs_are_flagged():
         assert _np(v["outcome"])[0, 0] == B.BAD_TOKEN
 
 
+@pytest.mark.parametrize("V,dtype,kind", [(4096, torch.bfloat16, "resident"), (70016, torch.bfloat16, "streamed")])
+def test_unusable_draft_record_is_flagged(V, dtype, kind):
+    """A draft record whose hub lies outside the vocabulary makes that node MDSD_BAD_PAIR (never a
+    wild read); every other node is verified as with the good records.  Invalid draft tokens
+    are flagged on the paths that take the records, too."""
+    wl = W.config(3, device=DEV, B=3, V=V, depth=3, seed=51)
+    pb = B.Problem.from_workload(wl).with_draft_stats()
+    rows = wl.B * wl.N
+    u_d = B.philox_uniform(51, 1, rows, 2, device=DEV).view(wl.B, wl.N, 2)
+    u_v = B.philox_uniform(51, 2, rows, 3, device=DEV).view(wl.B, wl.N, 3)
+    tokens = B.spechub_draft(pb, u_d)["tokens"]
+    good = B.spechub_verify(pb, tokens, u_v)
+    hubs = pb.draft_stats.view(torch.int32)[..., 2]
+    hubs[1, 0] = V + 5
+    hubs[2, 1] = -3
+    bad = B.spechub_verify(pb, tokens, u_v)
+    oc_g, oc_b, fl_b = _np(good["outcome"]), _np(bad["outcome"]), _np(bad["flags"])
+    assert oc_b[1, 0] == B.BAD_PAIR and fl_b[1, 0] & B.FLAG_BAD_PAIR
+    assert oc_b[2, 1] == B.BAD_PAIR and fl_b[2, 1] & B.FLAG_BAD_PAIR
+    keep = np.ones_like(oc_g, dtype=bool)
+    keep[1, 0] = keep[2, 1] = False
+    assert (oc_b[keep] == oc_g[keep]).all() and (_np(bad["token"])[keep] == _np(good["token"])[keep]).all()
+    # invalid tokens with records at hand (SpecHub and RRS take their own paths for them)
+    pb2 = B.Problem.from_workload(wl).with_draft_stats()
+    t2 = B.spechub_draft(pb2, u_d)["tokens"].clone()
+    t2[0, 1] = V + 1
+    v = B.spechub_verify(pb2, t2, u_v)
+    assert _np(v["outcome"])[0, 0] == B.BAD_TOKEN
+    pb3 = B.Problem.from_workload(wl).with_draft_stats()
+    t3 = B.rrs_draft(pb3, u_d)["tokens"].clone()
+    t3[0, 2] = -9
+    v = B.rrs_verify(pb3, t3, u_v)
+    assert _np(v["outcome"])[0, 0] == B.BAD_TOKEN and _np(v["flags"])[0, 0] & B.FLAG_BAD_TOKEN
+    assert (_np(v["outcome"])[1:] >= -1).all()
+
+
 @pytest.mark.parametrize("method", ["rrs", "rrsw"])
 def test_repeated_draft_tokens(method):
     """Duplicates handed to the verifiers (RRS draws them; RRSw must treat the second as massless)."""
