@@ -226,7 +226,7 @@ def main():
                    "step": "draft+verify+walk", "launch": "hip graph replay" if graphs else "three launches",
                    "input_copies_rotated": copies,
                    "early_exit": True,
-                   "draft_stats_handed_to_verify": args.method in ("spechub", "rrs") and not args.no_stats,
+                   "draft_stats_handed_to_verify": not args.no_stats,
                    "tokens_per_step_last_batch": tps},
         "roofline": {"bound": "hbm", "kernel": "%s_verify" % args.method, "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,

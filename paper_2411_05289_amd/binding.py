@@ -311,7 +311,7 @@ class StepPlan:
     def __init__(self, method: str, pb: Problem, u_draft, u_verify, *, flags=True, hand_stats=True):
         if method not in ("spechub", "rrs", "rrsw"):
             raise ValueError("unknown method %r" % method)
-        if method in ("spechub", "rrs") and hand_stats and pb.draft_stats is None:
+        if hand_stats and pb.draft_stats is None:
             pb = pb.with_draft_stats()   # spechub_draft -> spechub_verify hand-over of the row statistics
         B, N, _ = pb.draft.shape
         dev = pb.draft.device

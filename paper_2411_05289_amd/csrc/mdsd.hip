@@ -12,7 +12,7 @@
 //   resid   the vocabulary-wide residual sums of the method, one partial sum per slab in LDS
 //   draw    inverse-CDF search over the slab sums, then inside one slab
 // Kernel families, in the order of this file: helpers for the passes; the SpecHub kernel for
-// logit rows in registers (spechub_*_resident); the RRS kernel for the same (rrs_*_resident);
+// logit rows in registers (spechub_*_resident); the RRS / RRSw kernel for the same (rrs_*_resident);
 // the one-sweep statistics of streamed rows; the generic kernel for everything else
 // (verify_node); the draft kernel; tree walk; Philox; host-side validation, dispatch and the
 // C entry points.
@@ -850,13 +850,16 @@ __global__ __launch_bounds__(kWG, (NIT <= 8 ? 4 : 2)) void spechub_path_resident
     });
 }
 
-// ---------------------------------------------------------------- RRS with replacement, rows in registers
+// ---------------------------------------------------------------- RRS / RRSw, rows in registers
 // Alg. 1 for one internal node when the draft call left its record of the draft row (largest
 // stored element, total mass): the target row sits in registers, the draft row is streamed once
 // per rejected round, and a node whose first draft is accepted never reads it.  The state after
 // i rejections is the residual U = max(p - c q, 0) with mass W (c_1 = 0, W_0 = 1,
-// c_{i+1} = c_i + W_i): round i + 1 accepts x with probability U(x) / (W q(x)).
-template <int DT, int NIT, bool MASKED>
+// c_{i+1} = c_i + W_i rho_{i+1}): round i + 1 accepts x with probability U(x) / (W q_{i+1}(x)).
+// WO (without replacement): q_{i+1} is q without the tokens rejected so far, rescaled by
+// rho_{i+1} = (mass of q) / (mass left); the mass outside all k drafted tokens is summed (positive
+// terms only) in the first pass over the draft row, the masses left are that plus the later drafts'.
+template <int DT, int NIT, bool MASKED, bool WO>
 __device__ __forceinline__ void rrs_resident(const Params& P, const NodeId& id, const RowView& rp,
                                              const RowView& rq, const RowSrc<DT, NIT, MASKED>& sp,
                                              bool need_full, float* rprob, Shared& sh, int& phase, NodeOut& o)
@@ -920,12 +923,16 @@ __device__ __forceinline__ void rrs_resident(const Params& P, const NodeId& id, 
     float c = 0.f, Wc = 1.f;
     bool decided = false, slabs_current = false;
     int n_rej = 0;
-    // one pass over both rows: slab sums (and total) of max(p - c_new q, 0), rejected tokens masked
-    auto residual_pass = [&](float c_new) {
+    float rem_k = 0.f;  // WO: unnormalised draft mass outside all k drafted tokens (after the first pass)
+    // one pass over both rows: slab sums (and total) of max(p - c_new q, 0), rejected tokens masked;
+    // with want_rem also the draft mass outside the drafted tokens
+    auto residual_pass = [&](float c_new, bool want_rem) {
         const float c_iZq = c_new * iZq;
-        // slabs of the first two rejected tokens (with more than two, every slab takes the slow check)
+        // slabs of the first two tokens to mask (with more than two, every slab takes the slow check)
+        const int n_mask = want_rem ? k : n_rej;
         const int s_lo = (sh.node_x[0] + rp.head) / (64 * E);
-        const int s_hi = n_rej > 1 ? (sh.node_x[1] + rp.head) / (64 * E) : s_lo;
+        const int s_hi = n_mask > 1 ? (sh.node_x[1] + rp.head) / (64 * E) : s_lo;
+        float lane_rem = 0.f;
         SlabSums<NIT> sums;
         // Opaque copies: the weights of the target row do not change from round to round, and
         // the compiler would otherwise compute all of them once, ahead of the rounds, and hold
@@ -941,20 +948,35 @@ __device__ __forceinline__ void rrs_resident(const Params& P, const NodeId& id, 
                 unpack_half<DT, MASKED, hv>(dp, rp, ExpW::fill(), chunk, ep);
                 unpack_half<DT, MASKED, hv>(dq, rq, ExpW::fill(), chunk, eq);
 #pragma unroll
-                for (int e = 0; e < HE; ++e) w[e] = rrs_term(cpo(ep[e]), cq(eq[e]), iZp, c_iZq);
-                if (__builtin_expect(s == s_lo || s == s_hi || n_rej > 2, 0)) {
+                for (int e = 0; e < HE; ++e) {
+                    eq[e] = cq(eq[e]);
+                    w[e] = rrs_term(cpo(ep[e]), eq[e], iZp, c_iZq);
+                }
+                if (__builtin_expect(s == s_lo || s == s_hi || n_mask > 2, 0)) {
                     asm volatile("" ::: "memory");
-                    for (int j = 0; j < n_rej; ++j) {
+                    for (int j = 0; j < n_mask; ++j) {
                         const int xvj = sh.node_x[j] + rp.head;
 #pragma unroll
-                        for (int e = 0; e < HE; ++e)
-                            if (chunk * E + hv * HE + e == xvj) w[e] = 0.f;
+                        for (int e = 0; e < HE; ++e) {
+                            if (chunk * E + hv * HE + e == xvj) {
+                                if (j < n_rej) w[e] = 0.f;
+                                eq[e] = 0.f;  // only summed with want_rem, where every drafted token is left out
+                            }
+                        }
                     }
                 }
                 if constexpr (HE == 4)
                     part[hv] = (w[0] + w[1]) + (w[2] + w[3]);
                 else
                     part[hv] = w[0] + w[1];
+                if constexpr (WO) {
+                    if (want_rem) {
+                        if constexpr (HE == 4)
+                            lane_rem += (eq[0] + eq[1]) + (eq[2] + eq[3]);
+                        else
+                            lane_rem += eq[0] + eq[1];
+                    }
+                }
             };
             half(std::integral_constant<int, 0>{});
             __builtin_amdgcn_sched_barrier(0);
@@ -962,8 +984,26 @@ __device__ __forceinline__ void rrs_resident(const Params& P, const NodeId& id, 
             sums.put(it, part[0] + part[1]);
         });
         sums.store(sh.slab_w, rp.nslab);
+        if constexpr (WO) {
+            if (want_rem) {
+                float rr[1] = {lane_rem};
+                block_sum<kWaves, 1>(rr, sh.red, phase);
+                rem_k = rr[0];
+            }
+        }
         __syncthreads();
         return slab_total(rp.nslab, [&](int j) { return sh.slab_w[j]; });
+    };
+    // WO: unnormalised draft mass left before round i (i >= 1): what no draft took, plus the
+    // drafts still to come (a repeated token counts once)
+    auto mass_left = [&](int i) {
+        float m = rem_k;
+        for (int j = k - 1; j >= i; --j) {
+            bool dup = false;
+            for (int l = 0; l < j; ++l) dup = dup || (sh.node_x[l] == sh.node_x[j]);
+            if (!dup) m += cq(sh.node_lq[j]);
+        }
+        return m;
     };
 
     for (int i = 0; i < k; ++i) {
@@ -972,16 +1012,24 @@ __device__ __forceinline__ void rrs_resident(const Params& P, const NodeId& id, 
         bool seen = false;
         for (int j = 0; j < i; ++j) seen = seen || (sh.node_x[j] == xi);
         const float Ux = seen ? 0.f : fmaxf(fmaf(-c, qx, px), 0.f);
-        if (ui * qx * Wc < Ux) {  // Alg. 1 returns at the first acceptance
+        // draft probability of x_i in this round and the factor that rescales q; without
+        // replacement a repeated token has no mass left
+        float Qi = qx, rho = 1.f;
+        if (WO && i > 0) {
+            const float left = mass_left(i);
+            Qi = seen ? 0.f : cq(sh.node_lq[i]) / left;
+            rho = 1.f / (left * iZq);
+        }
+        if (ui * Qi * Wc < Ux) {  // Alg. 1 returns at the first acceptance
             o.outcome = i;
             o.token = xi;
             decided = true;
             break;
         }
-        const float c_new = c + Wc;
+        const float c_new = fmaf(Wc, rho, c);
         n_rej = i + 1;
         if (i > 0) __syncthreads();  // earlier readers of the slab sums are done
-        const float W_new = residual_pass(c_new);
+        const float W_new = residual_pass(c_new, WO && i == 0);
         if (W_new > 0.f) {
             c = c_new;
             Wc = W_new;
@@ -990,11 +1038,17 @@ __device__ __forceinline__ void rrs_resident(const Params& P, const NodeId& id, 
             o.flags |= MDSD_FLAG_ZERO_RESIDUAL;
             slabs_current = false;
         }
+        if constexpr (WO) {
+            if (!(mass_left(i + 1) > 0.f)) {
+                o.flags |= MDSD_FLAG_Q_EXHAUSTED;
+                break;
+            }
+        }
     }
     if (decided && !need_full) return;
     if (!slabs_current) {
         __syncthreads();
-        residual_pass(c);
+        residual_pass(c, false);
     }
     const float c_iZq = c * iZq;
     auto cw = [&](int s, float(&w)[E]) {
@@ -1017,7 +1071,7 @@ __device__ __forceinline__ void rrs_resident(const Params& P, const NodeId& id, 
     if (rprob) write_resid_prob<DT>(rprob, rp, W, cw);
 }
 
-template <int DT, int NIT, bool MASKED>
+template <int DT, int NIT, bool MASKED, bool WO>
 __device__ __forceinline__ NodeOut rrs_node_resident(const Params& P, const NodeId& id, Shared& sh, int& phase)
 {
     const bool need_full = (P.resid_mass != nullptr) || (P.resid_prob != nullptr);
@@ -1030,7 +1084,7 @@ __device__ __forceinline__ NodeOut rrs_node_resident(const Params& P, const Node
         leaf_resident<DT, NIT, MASKED>(P, rp, sp, P.u[id.row * (P.k + 1) + P.k], rprob, sh, phase, o);
     } else {
         const RowView rq = make_row<DT>(P.draft, P.ld_d, id.row, P.V);
-        rrs_resident<DT, NIT, MASKED>(P, id, rp, rq, sp, need_full, rprob, sh, phase, o);
+        rrs_resident<DT, NIT, MASKED, WO>(P, id, rp, rq, sp, need_full, rprob, sh, phase, o);
     }
     if (threadIdx.x == 0) {
         P.outcome[id.row] = o.outcome;
@@ -1041,12 +1095,12 @@ __device__ __forceinline__ NodeOut rrs_node_resident(const Params& P, const Node
     return o;
 }
 
-template <int DT, int NIT, bool MASKED>
+template <int DT, int NIT, bool MASKED, bool WO>
 __global__ __launch_bounds__(kWG, (NIT <= 8 ? kStatsWavesPerSimd : 2)) void rrs_verify_resident(const Params P)
 {
     __shared__ Shared sh;
     int phase = 0;
-    rrs_node_resident<DT, NIT, MASKED>(P, node_of_block(P), sh, phase);
+    rrs_node_resident<DT, NIT, MASKED, WO>(P, node_of_block(P), sh, phase);
 }
 
 // One sweep over a logit row that is streamed from memory (too long for registers), instead of
@@ -1396,8 +1450,8 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                 outcome = MDSD_BAD_TOKEN;
             } else {
                 // With replacement the draft call's record (largest stored element, total mass)
-                // stands in for the statistics of the draft row; without replacement the
-                // normaliser depends on the drafted tokens and the row is read.
+                // stands in for the statistics of the draft row; without replacement this kernel
+                // sums the row without the drafted tokens itself.
                 const bool have_stats = !WO && P.stats_in != nullptr;
                 mdsd_row_stats st{0.f, 0.f, -1, 0};
                 if (have_stats) st = P.stats_in[id.row];
@@ -1952,10 +2006,11 @@ static bool rrs_resident_covers(int dtype, int nit, bool masked)
     return nit > 0 && (dtype == MDSD_FP32 || (nit <= 8 && !masked));
 }
 
+template <bool WO>
 static void launch_rrs_resident(int dtype, int nit, bool masked, dim3 grid, dim3 block, hipStream_t st,
                                 const Params& P)
 {
-#define MDSD_LAUNCH_RRS(DT, N, M) hipLaunchKernelGGL((rrs_verify_resident<DT, N, M>), grid, block, 0, st, P)
+#define MDSD_LAUNCH_RRS(DT, N, M) hipLaunchKernelGGL((rrs_verify_resident<DT, N, M, WO>), grid, block, 0, st, P)
     if (dtype == MDSD_FP32) {
         if (nit == 4) {
             if (masked) MDSD_LAUNCH_RRS(0, 4, true); else MDSD_LAUNCH_RRS(0, 4, false);
@@ -1993,10 +2048,10 @@ static void launch_verify(const mdsd_problem* pb, const Params& P, bool path, hi
             launch_spechub_resident<1>(nit, rows_need_mask(pb), path, grid, block, st, P);
         return;
     }
-    if (METHOD == kRRS && lg && P.stats_in != nullptr && !path &&
+    if (METHOD != kSpecHub && lg && P.stats_in != nullptr && !path &&
         rrs_resident_covers(pb->dtype, nit, rows_need_mask(pb))) {
-        // with replacement, logit rows in registers, the draft call's records at hand
-        launch_rrs_resident(pb->dtype, nit, rows_need_mask(pb), grid, block, st, P);
+        // logit rows in registers, the draft call's records at hand
+        launch_rrs_resident<METHOD == kRRSw>(pb->dtype, nit, rows_need_mask(pb), grid, block, st, P);
         return;
     }
     // The generic RRS rounds hold many registers beside two resident rows (8 chunks per lane and
@@ -2087,7 +2142,7 @@ static int verify_entry(int method, const mdsd_problem* pb, const int32_t* token
     P.resid_mass = out->resid_mass;
     P.flags = out->flags;
     P.resid_prob = out->resid_prob;
-    P.stats_in = method != kRRSw ? pb->draft_stats : nullptr;
+    P.stats_in = pb->draft_stats;
     hipStream_t st = (hipStream_t)stream;
     (void)hipGetLastError();
     if (method == kSpecHub)
@@ -2113,7 +2168,7 @@ static int draft_entry(int method, const mdsd_problem* pb, const float* u, int32
     P.tokens_out = tokens;
     P.hub_out = hub;
     P.flags = flags;
-    P.stats_out = method != kRRSw ? pb->draft_stats : nullptr;
+    P.stats_out = pb->draft_stats;
     hipStream_t st = (hipStream_t)stream;
     (void)hipGetLastError();
     if (method == kSpecHub)
@@ -2252,6 +2307,6 @@ const char* mdsd_strerror(int code)
     }
 }
 
-int mdsd_version(void) { return 101; }
+int mdsd_version(void) { return 102; }
 
 }  // extern "C"

@@ -119,7 +119,7 @@ def check_case(method: str, wl: Workload, seed: int = 0, seqs=None, full_outputs
     g_path = VERIFY_PATH[method](pb, tokens, u_v, resid_mass=False, flags=True, walk=True)
     out["path_nodes_visited"] = _compare_path(wl, g_path, o_v, idx, near, "path")
 
-    if method in ("spechub", "rrs"):
+    if method in ("spechub", "rrs", "rrsw"):
         # ---- the same two stages with the draft call's row statistics handed to verify
         pb_s = pb.with_draft_stats()
         g_ds = DRAFT[method](pb_s, u_d)
