@@ -9,7 +9,7 @@ import torch
 import oracle
 from paper_2411_05289_amd import binding as B
 from paper_2411_05289_amd import workloads as W
-from parity import METHODS, check_case, tokens_per_step, _np
+from parity import DRAFT, METHODS, VERIFY, check_case, oracle_kwargs, tokens_per_step, uniforms, _np
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -279,6 +279,44 @@ def test_repeated_draft_tokens(method):
     near = o["margin"] < 1e-6
     assert ((_np(g["outcome"]) == o["outcome"]) | near).all()
     assert ((_np(g["token"]) == o["token"]) | near).all()
+
+
+def test_draft_mass_below_the_fp32_range_is_flagged():
+    """Rows so peaked (temperature 0.03) that, once the dominant token is removed, what is left is
+    below 2^-126 of it: the kernels' fp32 weights then hold no mass.  rrsw_draft repeats the token
+    and flags the node, spechub_draft gives the pair (a, a) and flags it, both verifiers still
+    return a valid outcome; where the rest is inside the range the tokens are the oracle's."""
+    wl = W.config(2, device=DEV, B=6, V=4104, k=2, depth=3, seed=300)
+    wl.temp_target, wl.temp_draft = 0.02, 0.03
+    pb = B.Problem.from_workload(wl)
+    u_d, u_v = uniforms(wl, 300)
+    rows = W.rows_as_numpy(wl.draft).astype(np.float64)
+    w = np.exp((rows - rows.max(axis=-1, keepdims=True)) / np.float64(np.float32(wl.temp_draft)))
+    internal = np.arange(wl.N) < W.internal_nodes(wl.k, wl.depth)
+    seen = {"gone": 0, "kept": 0}
+    for method, flag in (("rrsw", B.FLAG_Q_EXHAUSTED), ("spechub", B.FLAG_DEGENERATE_HUB)):
+        g = DRAFT[method](pb, u_d)
+        o = oracle.batch_draft(METHODS[method], W.rows_as_numpy(wl.draft), _np(u_d), temp_draft=wl.temp_draft,
+                               nthreads=8, **oracle_kwargs(wl))
+        g_tok, g_flags = _np(g["tokens"]), _np(g["flags"])
+        for b in range(wl.B):
+            for n in np.nonzero(internal)[0]:
+                c0 = wl.k * n + 1
+                first = o["tokens"][b, c0] if method == "rrsw" else int(np.argmax(w[b, n]))
+                rest = np.delete(w[b, n], first).sum()         # relative to the largest weight, 1
+                if method == "rrsw" and w[b, n, first] < 1.0:
+                    continue                                   # the dominant token was not drawn first
+                if np.delete(w[b, n], first).max() < 2.0 ** -150:   # every other weight rounds to 0
+                    seen["gone"] += 1
+                    assert g_flags[b, n] & flag, (method, b, n, rest)
+                    assert g_tok[b, c0] == g_tok[b, c0 + 1] == first, (method, b, n)
+                elif rest > 1e-30 and o["margin"][b, n] > 1e-6:
+                    seen["kept"] += 1
+                    assert (g_tok[b, c0:c0 + 2] == o["tokens"][b, c0:c0 + 2]).all(), (method, b, n)
+                    assert g_flags[b, n] == 0
+        v = VERIFY[method](pb, g["tokens"], u_v, flags=True, walk=True)
+        assert (_np(v["outcome"]) >= -1).all() and (_np(v["token"]) >= 0).all()
+    assert seen["gone"] > 0 and seen["kept"] > 0, seen
 
 
 # ----------------------------------------------------------------- determinism
