@@ -21,6 +21,8 @@
  *     problems (a token id outside [0,V), a SpecHub pair without the hub, a
  *     draft row whose whole mass sits on the hub, a residual without mass) are
  *     reported per node in `outcome` / `flags`, never by trapping.
+ *   - B = 0 is an empty batch: the call looks at nothing else, launches
+ *     nothing and returns MDSD_OK.
  *   - Trees: nodes in breadth-first order, root = node 0.  With first_child
  *     == NULL the tree is the complete k-ary tree with `depth` levels
  *     (N = (k^depth - 1)/(k - 1); Sec. 5.3 "binary trees of depth d with
@@ -62,7 +64,7 @@ extern "C" {
 /* status codes */
 #define MDSD_OK 0
 #define MDSD_E_NULL (-1)      /* a required pointer is NULL                     */
-#define MDSD_E_SHAPE (-2)     /* B < 1, N < 1, V < 2, ld < V, depth < 1, tree/N mismatch */
+#define MDSD_E_SHAPE (-2)     /* B < 0, N < 1, V < 2, ld < V, depth < 1, tree/N mismatch */
 #define MDSD_E_K (-3)         /* k outside 1..MDSD_MAX_K, or SpecHub with k != 2 (Sec. 4) */
 #define MDSD_E_TEMP (-4)      /* kind == logits and a temperature is not > 0    */
 #define MDSD_E_DTYPE (-5)     /* unknown dtype or kind                          */
@@ -235,7 +237,7 @@ int mdsd_tree_walk(const mdsd_problem* pb, const int32_t* outcome, const int32_t
  * SC'11).  out[row*slots + s] = (w >> 8) * 2^-24 with w = word (s & 3) of
  * Philox(counter = (row_lo, row_hi, s >> 2, stream_id), key = (seed_lo,
  * seed_hi)).  out: device [rows, slots] fp32; words: device [rows, slots]
- * uint32 or NULL (the raw words, for tests).
+ * uint32 or NULL (the raw words, for tests).  rows = 0 returns MDSD_OK at once.
  */
 int mdsd_philox_uniform(uint64_t seed, uint32_t stream_id, int64_t rows, int32_t slots,
                         float* out, uint32_t* words, void* stream);

@@ -1885,9 +1885,13 @@ static int complete_tree_nodes(int k, int depth, int64_t* n_internal)
     return (int)n;
 }
 
+// what validate returns for a batch of no trees: the entry points then return MDSD_OK at once
+static constexpr int kEmptyBatch = 1;
+
 static int validate(const mdsd_problem* pb, int method, bool need_target, Params* P)
 {
     if (!pb) return MDSD_E_NULL;
+    if (pb->B == 0) return kEmptyBatch;
     if (!pb->draft || (need_target && !pb->target)) return MDSD_E_NULL;
     if (pb->dtype != MDSD_FP32 && pb->dtype != MDSD_BF16) return MDSD_E_DTYPE;
     if (pb->kind != MDSD_PROBS && pb->kind != MDSD_LOGITS) return MDSD_E_DTYPE;
@@ -2128,6 +2132,7 @@ static int verify_entry(int method, const mdsd_problem* pb, const int32_t* token
 {
     Params P = {};
     const int rc = validate(pb, method, true, &P);
+    if (rc == kEmptyBatch) return MDSD_OK;
     if (rc != MDSD_OK) return rc;
     if (!tokens || !u || !out || !out->outcome || !out->token) return MDSD_E_NULL;
     if ((out->accept_depth == nullptr) != (out->emitted == nullptr)) return MDSD_E_NULL;
@@ -2162,6 +2167,7 @@ static int draft_entry(int method, const mdsd_problem* pb, const float* u, int32
 {
     Params P = {};
     const int rc = validate(pb, method, false, &P);
+    if (rc == kEmptyBatch) return MDSD_OK;
     if (rc != MDSD_OK) return rc;
     if (!u || !tokens) return MDSD_E_NULL;
     P.u = u;
@@ -2266,7 +2272,9 @@ int rrsw_verify_path(const mdsd_problem* pb, const int32_t* tokens, const float*
 int mdsd_tree_walk(const mdsd_problem* pb, const int32_t* outcome, const int32_t* token,
                    int32_t* accept_depth, int32_t* emitted, void* stream)
 {
-    if (!pb || !outcome || !token || !accept_depth || !emitted) return MDSD_E_NULL;
+    if (!pb) return MDSD_E_NULL;
+    if (pb->B == 0) return MDSD_OK;
+    if (!outcome || !token || !accept_depth || !emitted) return MDSD_E_NULL;
     if (pb->B < 1 || pb->N < 1 || pb->depth < 1) return MDSD_E_SHAPE;
     if (pb->k < 1 || pb->k > MDSD_MAX_K) return MDSD_E_K;
     (void)hipGetLastError();
@@ -2276,9 +2284,9 @@ int mdsd_tree_walk(const mdsd_problem* pb, const int32_t* outcome, const int32_t
 int mdsd_philox_uniform(uint64_t seed, uint32_t stream_id, int64_t rows, int32_t slots, float* out,
                         uint32_t* words, void* stream)
 {
-    if (!out && !words) return MDSD_E_NULL;
     if (rows < 0 || slots < 1) return MDSD_E_SHAPE;
     if (rows == 0) return MDSD_OK;
+    if (!out && !words) return MDSD_E_NULL;
     const int64_t n = rows * ((slots + 3) >> 2);
     const int threads = 256;
     const int64_t blocks = (n + threads - 1) / threads;

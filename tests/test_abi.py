@@ -46,7 +46,7 @@ def _problem(**kw):
 
 
 @pytest.mark.parametrize("kw,code", [
-    (dict(V=1), -2), (dict(B=0), -2), (dict(N=4), -2), (dict(ld_t=8), -2), (dict(depth=0), -2),
+    (dict(V=1), -2), (dict(B=-1), -2), (dict(N=4), -2), (dict(ld_t=8), -2), (dict(depth=0), -2),
     (dict(k=3, N=4), -3), (dict(k=0), -3), (dict(temp_target=0.0), -4), (dict(temp_draft=-1.0), -4),
     (dict(dtype=7), -5), (dict(kind=2), -5), (dict(target=0x1002, draft=0x2000), -6),
     (dict(target=0x1001), -6), (dict(draft=None), -1), (dict(ld_t=65), -6),
@@ -58,6 +58,21 @@ def test_spechub_verify_rejects_bad_problems(kw, code):
     res.outcome, res.token = 0x3000, 0x4000
     rc = L.spechub_verify(C.byref(p), C.c_void_p(0x5000), C.c_void_p(0x6000), C.byref(res), None, 0, None)
     assert rc == code
+
+
+def test_empty_batch_is_accepted_and_launches_nothing():
+    """B = 0: every entry point returns MDSD_OK before it looks at a pointer or the GPU."""
+    L = B.lib()
+    p = _problem(B=0, target=None, draft=None)
+    res = B._Result()
+    for f in (L.spechub_verify, L.rrs_verify, L.rrsw_verify, L.spechub_verify_path, L.rrs_verify_path,
+              L.rrsw_verify_path):
+        assert f(C.byref(p), None, None, C.byref(res), None, 0, None) == 0
+    assert L.spechub_draft(C.byref(p), None, None, None, None, None, 0, None) == 0
+    assert L.rrs_draft(C.byref(p), None, None, None, None, 0, None) == 0
+    assert L.rrsw_draft(C.byref(p), None, None, None, None, 0, None) == 0
+    assert L.mdsd_tree_walk(C.byref(p), None, None, None, None, None) == 0
+    assert L.mdsd_philox_uniform(1, 0, 0, 4, None, None, None) == 0
 
 
 def test_null_arguments():

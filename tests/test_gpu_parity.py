@@ -9,7 +9,7 @@ import torch
 import oracle
 from paper_2411_05289_amd import binding as B
 from paper_2411_05289_amd import workloads as W
-from parity import DRAFT, METHODS, VERIFY, check_case, oracle_kwargs, tokens_per_step, uniforms, _np
+from parity import DRAFT, METHODS, VERIFY, VERIFY_PATH, check_case, oracle_kwargs, tokens_per_step, uniforms, _np
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -279,6 +279,23 @@ def test_repeated_draft_tokens(method):
     near = o["margin"] < 1e-6
     assert ((_np(g["outcome"]) == o["outcome"]) | near).all()
     assert ((_np(g["token"]) == o["token"]) | near).all()
+
+
+@pytest.mark.parametrize("method", ALL)
+def test_empty_batch(method):
+    """No trees: every call succeeds and returns empty outputs."""
+    k, depth, V = 2, 3, 64
+    N = W.tree_nodes(k, depth)
+    rows = torch.empty((0, N, V), dtype=torch.bfloat16, device=DEV)
+    pb = B.Problem(rows, rows.clone(), B.LOGITS, k, depth).with_draft_stats()
+    d = DRAFT[method](pb, torch.empty((0, N, k), dtype=torch.float32, device=DEV))
+    assert d["tokens"].shape == (0, N)
+    u_v = torch.empty((0, N, k + 1), dtype=torch.float32, device=DEV)
+    for call in (VERIFY[method], VERIFY_PATH[method]):
+        v = call(pb, d["tokens"], u_v, flags=True, walk=True)
+        assert v["outcome"].shape == (0, N) and v["accept_depth"].shape == (0,) and v["emitted"].shape == (0, depth)
+    assert B.philox_uniform(1, 0, 0, 4, device=DEV).numel() == 0
+    torch.cuda.synchronize()
 
 
 def test_draft_mass_below_the_fp32_range_is_flagged():
