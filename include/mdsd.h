@@ -97,9 +97,8 @@ extern "C" {
  * MDSD_BAD_PAIR.  Results depend on the pointer only through fp32 rounding of rest_mass (a
  * different summation order).
  * rrs_draft and rrsw_draft write records too (hub = -1, rest_mass = the mass of the whole row,
- * before any token is removed) and rrs_verify / rrsw_verify read them the same way (rrsw_verify
- * on logit rows that its in-register kernel covers; elsewhere it ignores them).  Records must
- * come from the draft call of the same method.
+ * before any token is removed) and rrs_verify / rrsw_verify read them the same way.  Records
+ * must come from the draft call of the same method.
  */
 typedef struct mdsd_row_stats {
     float max_stored; /* largest stored element of the row (a logit, or a probability)        */

@@ -1449,10 +1449,11 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                 flags |= MDSD_FLAG_BAD_TOKEN;
                 outcome = MDSD_BAD_TOKEN;
             } else {
-                // With replacement the draft call's record (largest stored element, total mass)
-                // stands in for the statistics of the draft row; without replacement this kernel
-                // sums the row without the drafted tokens itself.
-                const bool have_stats = !WO && P.stats_in != nullptr;
+                // The draft call's record (largest stored element, total mass) stands in for the
+                // statistics of the draft row.  Without replacement the mass outside the drafted
+                // tokens is needed too, from the second round on: the first rejected round's pass
+                // over the draft row sums it.
+                const bool have_stats = P.stats_in != nullptr;
                 mdsd_row_stats st{0.f, 0.f, -1, 0};
                 if (have_stats) st = P.stats_in[id.row];
                 float z[2] = {0.f, 0.f};
@@ -1520,12 +1521,19 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                     });
                     block_sum<kWaves, 2>(z, sh.red, phase);
                 }
-                float eqx[MDSD_MAX_K], rem[MDSD_MAX_K + 1];
+                float eqx[MDSD_MAX_K];
                 for (int i = 0; i < k; ++i) eqx[i] = cq(load_elem<DT>(rq, xs[i]));
-                // rem[i] = draft mass (unnormalised) left before round i
-                rem[k] = z[1];
-                for (int i = k - 1; i >= 0; --i) rem[i] = rem[i + 1] + ((WO && !dup[i]) ? eqx[i] : 0.f);
-                const float Zq = rem[0];
+                // draft mass (unnormalised) left before round i: what no draft took (a sum of
+                // positive terms; with a record, known after the first rejected round) plus the
+                // drafts still to come, a repeated token counting once
+                const bool rem_pending = WO && have_stats;
+                float rem_k = rem_pending ? 0.f : z[1];
+                auto mass_left = [&](int i) {
+                    float m = rem_k;
+                    for (int j = k - 1; j >= i; --j) m += (WO && !dup[j]) ? eqx[j] : 0.f;
+                    return m;
+                };
+                const float Zq = have_stats ? z[1] : mass_left(0);
                 const float iZp = LOGITS ? 1.f / z[0] : 1.f;
                 const float iZq = LOGITS ? 1.f / Zq : 1.f;
 
@@ -1541,8 +1549,9 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                     // without replacement a repeated token has no mass left (Alg. 1, red lines)
                     float Qi = qx, rho = 1.f;
                     if (WO && i > 0) {
-                        Qi = dup[i] ? 0.f : eqx[i] / rem[i];
-                        rho = 1.f / (rem[i] * iZq);
+                        const float left = mass_left(i);
+                        Qi = dup[i] ? 0.f : eqx[i] / left;
+                        rho = 1.f / (left * iZq);
                     }
                     bool seen = false;
                     for (int j = 0; j < i; ++j) seen = seen || (xs[j] == xs[i]);
@@ -1558,14 +1567,27 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                     n_rej = i + 1;
                     if (i > 0) __syncthreads();  // earlier readers of slab_w are done
                     const float c_iZq = c_new * iZq;
+                    const bool want_rem = rem_pending && i == 0;
+                    float lane_rem[1] = {0.f};
                     need_q();
                     for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
-                        float w[E];
+                        float w[E], wq[E];
 #pragma unroll
-                        for (int e = 0; e < E; ++e) w[e] = rrs_term(cp(pa_[e]), cq(qa_[e]), iZp, c_iZq);
+                        for (int e = 0; e < E; ++e) {
+                            wq[e] = cq(qa_[e]);
+                            w[e] = rrs_term(cp(pa_[e]), wq[e], iZp, c_iZq);
+                        }
                         if (slab_has_excluded<E>(s, xv, n_rej)) zero_excluded<E>(w, chunk, xv, n_rej);
                         store_slab_sum(sh.slab_w, s, chunk_sum<E>(w));
+                        if (want_rem) {
+                            if (slab_has_excluded<E>(s, xv, k)) zero_excluded<E>(wq, chunk, xv, k);
+                            lane_rem[0] += chunk_sum<E>(wq);
+                        }
                     });
+                    if (want_rem) {
+                        block_sum<kWaves, 1>(lane_rem, sh.red, phase);
+                        rem_k = lane_rem[0];
+                    }
                     __syncthreads();
                     const float W_new = slab_total(rp.nslab, [&](int j) { return sh.slab_w[j]; });
                     if (W_new > 0.f) {
@@ -1578,7 +1600,7 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                         slab_c = -1.f;
                     }
                     if constexpr (WO) {
-                        if (!(rem[i + 1] > 0.f)) {
+                        if (!(mass_left(i + 1) > 0.f)) {
                             flags |= MDSD_FLAG_Q_EXHAUSTED;
                             break;
                         }
