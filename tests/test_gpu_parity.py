@@ -118,6 +118,47 @@ def test_padded_rows_and_offset_base(method, request):
     note(request, check_case(method, wl_c, seed=4))
 
 
+@pytest.mark.parametrize("method", ALL)
+def test_random_shapes_strides_and_temperatures(method, request):
+    """Seeded random cases: vocabulary size (ragged tails, one slab to many), k, depth, storage
+    type, logits or probabilities, both temperatures, row padding and a base address that is
+    not 16-byte aligned, straight against the oracle."""
+    rng = np.random.default_rng({"spechub": 1, "rrs": 2, "rrsw": 3}[method])
+    totals = {}
+    for case in range(24):
+        V = int(rng.choice([rng.integers(2, 40), rng.integers(40, 700), rng.integers(700, 9000)]))
+        k = 2 if method == "spechub" else int(rng.integers(1, 6))
+        depth = int(rng.integers(1, 4 if k <= 3 else 3))
+        N = W.tree_nodes(k, depth)
+        Bn = int(rng.integers(1, 7))
+        bf16 = bool(rng.integers(0, 2))
+        logits = bool(rng.integers(0, 4))             # one case in four: probabilities
+        dtype = torch.bfloat16 if bf16 and logits else torch.float32
+        pad, off = int(rng.integers(0, 18)), int(rng.integers(0, 8))
+        if logits:
+            t, d = W.llm_like_logits(Bn, N, V, logit_std=float(rng.uniform(0.5, 4.0)),
+                                     draft_noise_std=float(rng.uniform(0.2, 2.5)), dtype=dtype,
+                                     seed=100 + case, device=DEV)
+            temps = (float(rng.uniform(0.3, 2.0)), float(rng.uniform(0.3, 2.0)))
+        else:
+            t, d = W.dirichlet_rows(Bn, N, V, seed=100 + case, device=DEV)
+            temps = (1.0, 1.0)
+        ld = V + pad
+        big_t = torch.zeros((Bn * N * ld + off,), dtype=dtype, device=DEV)
+        big_d = torch.zeros((Bn * N * ld + off,), dtype=dtype, device=DEV)
+        tv = big_t[off:].view(Bn, N, ld)[:, :, :V]
+        dv = big_d[off:].view(Bn, N, ld)[:, :, :V]
+        tv.copy_(t)
+        dv.copy_(d)
+        wl = W.Workload("random%d" % case, Bn, N, V, k, depth, "bf16" if dtype == torch.bfloat16 else "fp32",
+                        "logits" if logits else "probs", temps[0], temps[1], tv, dv)
+        out = check_case(method, wl, seed=200 + case, full_outputs=V <= 3000)
+        for key, val in out.items():
+            if isinstance(val, (int, np.integer)):
+                totals[key] = totals.get(key, 0) + int(val)
+    note(request, totals)
+
+
 # ----------------------------------------------------------------- temperatures
 @pytest.mark.parametrize("method", ALL)
 @pytest.mark.parametrize("T", [0.3, 0.7, 2.0])
