@@ -1,18 +1,24 @@
-"""Build the HIP library (gfx950) in-tree: ``python -m paper_2411_05289_amd.build``."""
+"""Build the HIP library (gfx950) in-tree: ``python -m paper_2411_05289_amd.build``.
+
+Every ``csrc/*.hip`` file is one kernel family (or the host side) and is compiled to an object
+of its own, several at a time; the objects are then linked into ``libmdsd.so``."""
 from __future__ import annotations
 
 import os
+import shutil
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmdsd.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-ffp-contract=off",                       # fused multiply-adds only where written
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wextra", "-Wno-unused-parameter",
@@ -24,13 +30,36 @@ def sources():
     return [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith(".hip")]
 
 
+def jobs() -> int:
+    try:
+        n = int(os.environ.get("MAX_JOBS", "0"))
+    except ValueError:
+        n = 0
+    return max(1, min(n or (os.cpu_count() or 1), 16))
+
+
 def build(verbose: bool = True, extra=()) -> str:
-    tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [HIPCC, *FLAGS, *extra, "-o", tmp, *sources()]
+    tag = ".tmp%d" % os.getpid()
+    shutil.rmtree(OBJ, ignore_errors=True)
+    os.makedirs(OBJ)
+
+    def compile_one(src: str) -> str:
+        obj = os.path.join(OBJ, os.path.basename(src)[:-4] + ".o")
+        cmd = [HIPCC, *FLAGS, *extra, "-c", "-o", obj, src]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=jobs()) as pool:
+        objs = list(pool.map(compile_one, sources()))
+    tmp = LIB + tag
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
     os.replace(tmp, LIB)
+    shutil.rmtree(OBJ, ignore_errors=True)
     return LIB
 
 

@@ -1,0 +1,212 @@
+// The draft kernel: the k draft tokens of every internal node (SpecHub: the pair from Q;
+// RRS: k independent draws; RRSw: k draws without replacement), and the record of the draft row
+// that the verify call can take over.  Instantiated per method in draft_*.hip.
+#pragma once
+#include "launch.h"
+
+namespace mdsd {
+
+// ---------------------------------------------------------------- draft kernel
+template <int DT, bool LOGITS, int METHOD, int NIT, bool MASKED = true>
+__global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    using CV = ToWeight<LOGITS>;
+    __shared__ Shared sh;
+    int phase = 0;
+    // one workgroup per node; a leaf only records that it has no hub
+    const NodeId id = node_of_block(P);
+    const int b = id.b, n = id.n, c0 = id.c0;
+    const int64_t row = id.row;
+    if (n == 0 && threadIdx.x == 0) P.tokens_out[(int64_t)b * P.N] = -1;
+    if (c0 < 0) {
+        if (threadIdx.x == 0) {
+            if (P.hub_out) P.hub_out[row] = -1;
+            if (P.flags) P.flags[row] = 0;
+            if (P.stats_out) P.stats_out[row] = mdsd_row_stats{0.f, 0.f, -1, 0};
+        }
+        return;
+    }
+    const int k = P.k;
+    const float* ur = P.u + row * k;
+    const RowView rq = make_row<DT>(P.draft, P.ld_d, row, P.V);
+    RowSrc<DT, NIT, MASKED> sq;
+    sq.init(rq, CV::fill());
+    int32_t* xt = P.tokens_out + (int64_t)b * P.N + c0;
+    int flags = 0;
+
+    CV cq{0.f, 0.f};
+    int a_virt = rq.head;
+    float mm[1] = {0.f};
+    bool swept = false;
+    if constexpr (LOGITS && NIT == 0) {
+        // a streamed logit row: maximum, weights and slab sums in one sweep
+        float Z, mq_lane;
+        cq.s = kLog2e / P.temp_draft;
+        swept = sweep_streamed_row<DT, true>(sq, cq.s, sh, phase, mm[0], Z, &mq_lane);
+        if (swept) {
+            cq.ms = mm[0] * cq.s;
+            if constexpr (METHOD == kSpecHub) a_virt = block_argmax(sq, mq_lane, mm[0], sh, phase);
+        }
+    }
+    if (!swept) {
+        if (LOGITS || METHOD == kSpecHub) {
+            const float mq_lane = lane_max(sq);
+            mm[0] = mq_lane;
+            block_max<kWaves, 1>(mm, sh.red, phase);
+            if constexpr (METHOD == kSpecHub) a_virt = block_argmax(sq, mq_lane, mm[0], sh, phase);
+            if constexpr (LOGITS) {
+                cq.s = kLog2e / P.temp_draft;
+                cq.ms = mm[0] * cq.s;
+            }
+        }
+        pass_weights_to_slabs<CV>(sq, cq, nullptr, 0, sh.slab_w);
+    }
+    __syncthreads();
+
+    // slab sums with some tokens removed: only the slabs holding a removed token change,
+    // and those are recomputed with the tokens masked (never by subtraction)
+    int excl[MDSD_MAX_K];
+    int ov_slab[MDSD_MAX_K];
+    float ov_val[MDSD_MAX_K];
+    int n_excl = 0, n_ov = 0;
+    auto sv = [&](int i) {
+        float v = sh.slab_w[i];
+        for (int j = 0; j < n_ov; ++j)
+            if (ov_slab[j] == i) v = ov_val[j];
+        return v;
+    };
+    // this lane's weights of one chunk of slab s, removed tokens counting 0: from memory when the
+    // row is streamed, from the registers of the wave that owns the slab when it is resident
+    auto cw = [&](int s, float(&w)[E]) { chunk_weights<DT, CV>(rq, cq, excl, n_excl, s, w); };
+    auto cw_reg = [&](int it, float(&w)[E]) {
+        if constexpr (NIT > 0) {
+            float a[E];
+            get_dyn(sq, it, a);
+#pragma unroll
+            for (int e = 0; e < E; ++e) w[e] = cq(a[e]);
+            zero_excluded<E>(w, ((it * kWaves + wave_id()) * 64 + (int)(threadIdx.x & 63)), excl, n_excl);
+        }
+    };
+    auto draw = [&](float u, float W) {
+        if constexpr (NIT > 0) {
+            // draws with replacement follow each other with no barrier in between: the result
+            // slot in LDS must have been read by every wave before the next draw writes it
+            if constexpr (METHOD == kRRS) __syncthreads();
+            return __builtin_amdgcn_readfirstlane(draw_resident<E>(rq.nslab, u, W, sv, cw_reg, sh));
+        } else {
+            return icdf_slabs<E>(rq.nslab, u, W, sv, cw);
+        }
+    };
+    auto remove_token = [&](int v) {
+        excl[n_excl++] = v;
+        const int s = v / (64 * E);
+        float t;
+        if constexpr (NIT > 0) {
+            if (wave_id() == s % kWaves) {
+                float w[E];
+                cw_reg(s / kWaves, w);
+                const float ts = wave_sum(chunk_sum<E>(w));
+                if ((threadIdx.x & 63) == 0) sh.bcast_f = ts;
+            }
+            __syncthreads();
+            t = sh.bcast_f;
+        } else {
+            float w[E];
+            cw(s, w);
+            t = wave_sum(chunk_sum<E>(w));
+        }
+        int j = 0;
+        while (j < n_ov && ov_slab[j] != s) ++j;
+        ov_slab[j] = s;
+        ov_val[j] = t;
+        if (j == n_ov) ++n_ov;
+    };
+
+    int out_tok[MDSD_MAX_K];
+    if constexpr (METHOD == kSpecHub) {
+        const float W = slab_total(rq.nslab, sv);
+        const int v = draw(ur[0], W);
+        // the mass outside the hub: for the second draw, and for the verify call if it asked
+        float W2 = 0.f;
+        if (v == a_virt || P.stats_out) {
+            remove_token(a_virt);
+            W2 = slab_total(rq.nslab, sv);
+            if (P.stats_out && threadIdx.x == 0)
+                P.stats_out[row] = mdsd_row_stats{mm[0], W2, a_virt - rq.head, 0};
+        }
+        if (v != a_virt) {
+            out_tok[0] = v < 0 ? -1 : v - rq.head;
+            out_tok[1] = a_virt - rq.head;
+        } else {
+            int v2 = draw(ur[1], W2);
+            if (v2 < 0) {
+                v2 = a_virt;
+                flags |= MDSD_FLAG_DEGENERATE_HUB;
+            }
+            out_tok[0] = a_virt - rq.head;
+            out_tok[1] = v2 - rq.head;
+        }
+    } else {
+        int prev = rq.head;
+        for (int i = 0; i < k; ++i) {
+            const float W = slab_total(rq.nslab, sv);
+            if (i == 0 && P.stats_out && threadIdx.x == 0)  // with replacement: maximum and total mass
+                P.stats_out[row] = mdsd_row_stats{mm[0], W, -1, 0};
+            int v = draw(ur[i], W);
+            if (v < 0) {
+                v = prev;
+                flags |= MDSD_FLAG_Q_EXHAUSTED;
+            } else if (METHOD == kRRSw) {
+                remove_token(v);
+            }
+            prev = v;
+            out_tok[i] = v - rq.head;
+        }
+    }
+    if (threadIdx.x == 0) {
+        for (int i = 0; i < k; ++i) xt[i] = out_tok[i];
+        if (P.hub_out) P.hub_out[row] = (METHOD == kSpecHub) ? a_virt - rq.head : -1;
+        if (P.flags) P.flags[row] = flags;
+    }
+}
+
+template <int DT, bool LG, int METHOD>
+static void launch_draft_n(int nit, bool masked, dim3 grid, dim3 block, hipStream_t st, const Params& P)
+{
+    // rows that need no masking of their first and last chunk: a variant without the checks,
+    // for the two common register sizes
+    if (!masked && nit == 4) {
+        hipLaunchKernelGGL((draft_kernel<DT, LG, METHOD, 4, false>), grid, block, 0, st, P);
+        return;
+    }
+    if (!masked && nit == 8) {
+        hipLaunchKernelGGL((draft_kernel<DT, LG, METHOD, 8, false>), grid, block, 0, st, P);
+        return;
+    }
+    switch (nit) {
+    case 4: hipLaunchKernelGGL((draft_kernel<DT, LG, METHOD, 4>), grid, block, 0, st, P); break;
+    case 8: hipLaunchKernelGGL((draft_kernel<DT, LG, METHOD, 8>), grid, block, 0, st, P); break;
+    case 16: hipLaunchKernelGGL((draft_kernel<DT, LG, METHOD, 16>), grid, block, 0, st, P); break;
+    default: hipLaunchKernelGGL((draft_kernel<DT, LG, METHOD, 0>), grid, block, 0, st, P); break;
+    }
+}
+
+template <int METHOD>
+static void launch_draft_method(int dtype, bool logits, int nit, bool masked, dim3 grid, dim3 block, hipStream_t st,
+                                const Params& P)
+{
+    if (dtype == MDSD_FP32) {
+        if (logits)
+            launch_draft_n<0, true, METHOD>(nit, masked, grid, block, st, P);
+        else
+            launch_draft_n<0, false, METHOD>(nit, masked, grid, block, st, P);
+    } else {
+        if (logits)
+            launch_draft_n<1, true, METHOD>(nit, masked, grid, block, st, P);
+        else
+            launch_draft_n<1, false, METHOD>(nit, masked, grid, block, st, P);
+    }
+}
+
+}  // namespace mdsd

@@ -1,0 +1,482 @@
+// Device code shared by every kernel family of the library: the parameter block, the LDS
+// layout of a workgroup, the node a workgroup owns, the passes over a row (maximum, argmax,
+// weights to slab sums, draws), the element arithmetic of the three methods, the leaf case,
+// the path-only walk and the one-sweep statistics of a streamed row.
+//
+// One workgroup of 512 threads (8 wavefronts) owns one tree node -- or, in the path-only
+// kernels, one tree, whose visited nodes it handles one after another.  A node's work is a few
+// passes over its target row and, if it has children, its draft row, each pass a sequence of
+// fully coalesced 16-byte loads or a sweep over registers that hold the row:
+//   shift   a softmax shift for the stored logits: the row maximum, or a cheap estimate of it
+//           (and the hub = argmax of the draft row, unless the draft call handed it on)
+//   norm    softmax normalisers, sum of 2^((l - shift) * log2e / T)
+//   test    scalar look-ups of p(x), q(x) at the draft tokens and the first acceptance test;
+//           most nodes end here
+//   resid   the vocabulary-wide residual sums of the method, one partial sum per slab in LDS
+//   draw    inverse-CDF search over the slab sums, then inside one slab
+#pragma once
+#include <hip/hip_runtime.h>
+#include <type_traits>
+#include <limits.h>
+#include <stdlib.h>
+#include <stdint.h>
+
+#include "mdsd.h"
+#include "resident.h"
+#include "scan_core.h"
+
+namespace mdsd {
+
+enum Method { kSpecHub = 0, kRRS = 1, kRRSw = 2 };
+
+// SpecHub verify with draft statistics: chunks of the draft row requested ahead of their use in
+// the residual pass (one is enough: a chunk pair is about 150 instructions of work for each of
+// the 6 waves that share a SIMD), and the waves per SIMD the kernel is held to (6 = 80
+// registers per lane = three workgroups per compute unit; 8 would spill).
+constexpr int kStreamAhead = 1;
+constexpr int kStatsWavesPerSimd = 6;
+
+struct Params {
+    const void* target;
+    const void* draft;
+    int64_t ld_t, ld_d;
+    float temp_target, temp_draft;
+    int B, N, V, k, depth, n_internal;
+    const int32_t* first_child;
+    const int32_t* tokens;
+    const float* u;
+    int32_t* outcome;
+    int32_t* token;
+    float* resid_mass;
+    int32_t* flags;
+    float* resid_prob;
+    int32_t* accept_depth;  // path-only kernels
+    int32_t* emitted;
+    // draft kernels
+    int32_t* tokens_out;
+    int32_t* hub_out;
+    // draft-row statistics: written by the SpecHub draft kernel, read by the SpecHub verify kernel
+    mdsd_row_stats* stats_out;
+    const mdsd_row_stats* stats_in;
+};
+
+struct Shared {
+    BlockScratch<kWaves> red;
+    float slab_w[kMaxSlabs];
+    float bcast_f;  // one value handed from one lane to the workgroup
+    int bcast_i;
+    // RRS path for rows in registers: the node's draft tokens, the stored logits at them, the uniforms
+    int node_x[MDSD_MAX_K];
+    float node_lp[MDSD_MAX_K], node_lq[MDSD_MAX_K], node_u[MDSD_MAX_K + 1];
+};
+
+// Node of this workgroup.  Complete trees: nodes with children first (they
+// scan two rows), leaves after, so the long workgroups start early.
+struct NodeId {
+    int b, n, c0;
+    int64_t row;
+};
+
+__device__ __forceinline__ NodeId node_of_item(const Params& P, int w)
+{
+    NodeId id;
+    if (P.first_child == nullptr) {
+        const int total_int = P.B * P.n_internal;
+        if (w < total_int) {
+            id.b = w / P.n_internal;
+            id.n = w - id.b * P.n_internal;
+            id.c0 = P.k * id.n + 1;
+        } else {
+            w -= total_int;
+            const int n_leaf = P.N - P.n_internal;
+            id.b = w / n_leaf;
+            id.n = P.n_internal + (w - id.b * n_leaf);
+            id.c0 = -1;
+        }
+    } else {
+        id.b = w / P.N;
+        id.n = w - id.b * P.N;
+        id.c0 = P.first_child[id.n];
+        // an entry that leaves no room for k children is treated as a leaf
+        if (id.c0 < 1 || id.c0 + P.k > P.N) id.c0 = -1;
+    }
+    id.row = (int64_t)id.b * P.N + id.n;
+    return id;
+}
+
+__device__ __forceinline__ NodeId node_of_block(const Params& P) { return node_of_item(P, blockIdx.x); }
+
+// ---------------------------------------------------------------- passes
+// max of the stored values this lane holds
+template <class Src>
+__device__ __forceinline__ float lane_max(const Src& src)
+{
+    constexpr int E = Src::E;
+    float m = -__builtin_inff();
+    src.for_each([&](int, int, const float(&a)[E]) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) m = fmaxf(m, a[e]);
+    });
+    return m;
+}
+
+// lowest virtual index at which this lane holds the value m (INT_MAX: nowhere)
+template <class Src>
+__device__ __forceinline__ int lane_first_index_of(const Src& src, float m)
+{
+    constexpr int E = Src::E;
+    int idx = INT_MAX;
+    src.for_each([&](int, int chunk, const float(&a)[E]) {
+#pragma unroll
+        for (int e = E - 1; e >= 0; --e)
+            if (a[e] == m) idx = min(idx, chunk * E + e);
+    });
+    return idx;
+}
+
+// hub = lowest index among the maxima of the stored draft row (virtual index).
+// Only lanes that hold the maximum look for its position.
+template <class Src>
+__device__ __forceinline__ int block_argmax(const Src& src, float m_lane, float m_block, Shared& sh,
+                                            int& phase)
+{
+    int idx = INT_MAX;
+    if (m_lane == m_block) idx = lane_first_index_of(src, m_block);
+    const int a = block_min_index<kWaves>(idx, sh.red, phase);
+    return a == INT_MAX ? src.r.head : a;  // a row of NaNs has no maximum: stay in bounds
+}
+
+// zero the entries of one chunk whose virtual index is listed in excl
+template <int E>
+__device__ __forceinline__ void zero_excluded(float (&w)[E], int chunk, const int* excl, int n_excl)
+{
+    for (int j = 0; j < n_excl; ++j) {
+        const int off = excl[j] - chunk * E;
+#pragma unroll
+        for (int e = 0; e < E; ++e) w[e] = (e == off) ? 0.f : w[e];
+    }
+}
+
+// slab holds one of the excluded elements?
+template <int E>
+__device__ __forceinline__ bool slab_has_excluded(int s, const int* excl, int n_excl)
+{
+    bool hit = false;
+    for (int j = 0; j < n_excl; ++j) hit = hit || (excl[j] / (64 * E) == s);
+    return hit;
+}
+
+// weights of one row, one slab sum per slab left in LDS; elements listed in
+// excl count as 0
+template <class CV, class Src>
+__device__ __forceinline__ void pass_weights_to_slabs(const Src& src, CV cv, const int* excl, int n_excl,
+                                                      float* slab_w)
+{
+    constexpr int E = Src::E;
+    if constexpr (Src::kNit > 0) {
+        SlabSums<Src::kNit> sums;
+        src.for_each_it([&](int it, int s, int chunk, const float(&a)[E]) {
+            float w[E];
+#pragma unroll
+            for (int e = 0; e < E; ++e) w[e] = cv(a[e]);
+            if (slab_has_excluded<E>(s, excl, n_excl)) zero_excluded<E>(w, chunk, excl, n_excl);
+            sums.put(it, chunk_sum<E>(w));
+        });
+        sums.store(slab_w, src.r.nslab);
+    } else {
+        src.for_each([&](int s, int chunk, const float(&a)[E]) {
+            float w[E];
+#pragma unroll
+            for (int e = 0; e < E; ++e) w[e] = cv(a[e]);
+            if (slab_has_excluded<E>(s, excl, n_excl)) zero_excluded<E>(w, chunk, excl, n_excl);
+            store_slab_sum(slab_w, s, chunk_sum<E>(w));
+        });
+    }
+}
+
+// this lane's chunk of slab s of the same weights, read from memory (the draw
+// inside one slab; the slab index is only known at run time)
+template <int DT, class CV>
+__device__ __forceinline__ void chunk_weights(const RowView& r, CV cv, const int* excl, int n_excl, int s,
+                                              float (&w)[Elem<DT>::kPerChunk])
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    const int chunk = s * 64 + (threadIdx.x & 63);
+    float a[E];
+    load_chunk<DT>(r, chunk, CV::fill(), a);
+#pragma unroll
+    for (int e = 0; e < E; ++e) w[e] = cv(a[e]);
+    zero_excluded<E>(w, chunk, excl, n_excl);
+}
+
+// Draw from the weights of one row (slab sums already in LDS and visible).
+template <int DT, class CV>
+__device__ __forceinline__ int draw_from_row(const RowView& r, CV cv, const int* excl, int n_excl,
+                                             const float* slab_w, float u, float& W)
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    auto sv = [&](int i) { return slab_w[i]; };
+    W = slab_total(r.nslab, sv);
+    return icdf_slabs<E>(r.nslab, u, W, sv,
+                         [&](int s, float(&w)[E]) { chunk_weights<DT, CV>(r, cv, excl, n_excl, s, w); });
+}
+
+// ---------------------------------------------------------------- SpecHub element arithmetic
+// App. B.2 for one token y != a, from unnormalised weights ep, eq:
+//   P = ep/Zp, Q = eq/Zq, p' = max(P - Q, 0), Q'(y,a) = max(Q - P, 0),
+//   t = c Q - p'  ->  Q'(a,y) = max(t, 0),  p''(y) = max(-t, 0).
+struct HubScal {
+    float iZp, iZq, c;
+};
+
+__device__ __forceinline__ float clamp01(float x) { return __builtin_amdgcn_fmed3f(x, 0.f, 1.f); }
+
+// Every term is a probability (<= 1), so max(x, 0) is written as a clamp to [0, 1], which the
+// hardware applies for free on the instruction that produces x.
+__device__ __forceinline__ void spechub_terms(float ep, float eq, const HubScal& h, float& q_xa_res,
+                                              float& q_ax_res, float& w)
+{
+    const float Pn = ep * h.iZp;
+    const float Qn = eq * h.iZq;
+    q_xa_res = clamp01(Qn - Pn);                // Q'(y,a) = max(Q - P, 0)
+    const float pr = clamp01(Pn - Qn);          // p'(y)   = max(P - Q, 0)
+    q_ax_res = clamp01(fmaf(h.c, Qn, -pr));     // Q'(a,y) = max(c Q - p', 0)
+    w = clamp01(fmaf(-h.c, Qn, pr));            // p''(y)  = max(p' - c Q, 0)
+}
+
+template <int DT, class CV>
+__device__ __forceinline__ void spechub_chunk_w(const RowView& rp, const RowView& rq, CV cp, CV cq,
+                                                const HubScal& h, int a_virt, int s,
+                                                float (&w)[Elem<DT>::kPerChunk])
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    const int chunk = s * 64 + (threadIdx.x & 63);
+    float a[E], b[E];
+    load_chunk<DT>(rp, chunk, CV::fill(), a);
+    load_chunk<DT>(rq, chunk, CV::fill(), b);
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        float ep = cp(a[e]), eq = cq(b[e]);
+        if (chunk * E + e == a_virt) ep = eq = 0.f;
+        float s2, s1;
+        spechub_terms(ep, eq, h, s2, s1, w[e]);
+    }
+}
+
+// RRS residual weight for one token: max(p - c q, 0), c folded with 1/Zq
+__device__ __forceinline__ float rrs_term(float ep, float eq, float iZp, float c_iZq)
+{
+    return fmaxf(fmaf(-c_iZq, eq, ep * iZp), 0.f);
+}
+
+template <int DT, class CV>
+__device__ __forceinline__ void rrs_chunk_w(const RowView& rp, const RowView& rq, CV cp, CV cq, float iZp,
+                                            float c_iZq, const int* excl, int n_excl, int s,
+                                            float (&w)[Elem<DT>::kPerChunk])
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    const int chunk = s * 64 + (threadIdx.x & 63);
+    float a[E], b[E];
+    load_chunk<DT>(rp, chunk, CV::fill(), a);
+    load_chunk<DT>(rq, chunk, CV::fill(), b);
+#pragma unroll
+    for (int e = 0; e < E; ++e) w[e] = rrs_term(cp(a[e]), cq(b[e]), iZp, c_iZq);
+    zero_excluded<E>(w, chunk, excl, n_excl);
+}
+
+// write norm(w) of a whole row (diagnostic output)
+template <int DT, class ChunkW>
+__device__ __forceinline__ void write_resid_prob(float* out, const RowView& r, float W, ChunkW cw)
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    const int lane = threadIdx.x & 63, wave = wave_id();
+    const float iW = W > 0.f ? 1.f / W : 0.f;
+    for (int s = wave; s < r.nslab; s += kWaves) {
+        float w[E];
+        cw(s, w);
+        const int v0 = (s * 64 + lane) * E;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const int v = v0 + e;
+            if (v >= r.head && v < r.nvirt) out[v - r.head] = w[e] * iW;
+        }
+    }
+}
+
+// ---------------------------------------------------------------- single-read paths (logits in registers)
+struct NodeOut {
+    int outcome, token, flags;
+    float rmass;
+};
+
+using ExpW = ToWeight<true>;  // 2^(l*s - ms)
+
+// Draw from weights held in registers: slab search by every wave, the search inside the slab by
+// the wave that owns it; the result travels through LDS.  weights_of(it, w) gives this lane's
+// weights of its register chunk `it` (run-time value).
+template <int E, class SlabVal, class RegWeights>
+__device__ __forceinline__ int draw_resident(int nslab, float u, float W, SlabVal sv, RegWeights weights_of,
+                                             Shared& sh)
+{
+    SlabHit h;
+    if (!icdf_find_slab(nslab, u, W, sv, h)) return -1;  // same decision in every wave
+    if (wave_id() == h.slab % kWaves) {
+        float w[E];
+        weights_of(h.slab / kWaves, w);
+        const int v = icdf_in_slab<E>(w, h);
+        if ((threadIdx.x & 63) == 0) sh.bcast_i = v;
+    }
+    __syncthreads();
+    return sh.bcast_i;
+}
+
+// leaf: bonus token ~ p (the k = 0 case of Alg. 1)
+template <int DT, int NIT, bool MASKED>
+__device__ __forceinline__ void leaf_resident(const Params& P, const RowView& rp,
+                                              const RowSrc<DT, NIT, MASKED>& sp, float u, float* rprob,
+                                              Shared& sh, int& phase, NodeOut& o)
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    using Src = RowSrc<DT, NIT, MASKED>;
+    ExpW cp;
+    cp.s = kLog2e / P.temp_target;
+    auto sv = [&](int i) { return sh.slab_w[i]; };
+    float W;
+    // the cheap estimate of the maximum as the shift where there is one; if the weights
+    // overflowed or vanished with it, once more with the maximum itself
+    auto slab_sums = [&](float lane_m) {
+        float mm[1] = {lane_m};
+        block_max<kWaves, 1>(mm, sh.red, phase);
+        cp.ms = mm[0] * cp.s;
+        pass_weights_to_slabs<ExpW>(sp, cp, nullptr, 0, sh.slab_w);
+        __syncthreads();
+        return slab_total(rp.nslab, sv);
+    };
+    if constexpr (Src::kHasShiftEstimate) {
+        W = slab_sums(sp.lane_shift_estimate());
+        if (__builtin_expect(!(W > 0.f && W < __builtin_inff()), 0)) {
+            __syncthreads();  // every wave has read the slab sums that are about to be rewritten
+            W = slab_sums(lane_max(sp));
+        }
+    } else {
+        W = slab_sums(lane_max(sp));
+    }
+    const int v = draw_resident<E>(rp.nslab, u, W, sv, [&](int it, float(&w)[E]) {
+        float a[E];
+        get_dyn(sp, it, a);
+#pragma unroll
+        for (int e = 0; e < E; ++e) w[e] = cp(a[e]);
+    }, sh);
+    o.token = v < 0 ? -1 : v - rp.head;
+    if (v < 0) o.flags |= MDSD_FLAG_ZERO_RESIDUAL;
+    o.rmass = 1.f;
+    if (rprob)
+        write_resid_prob<DT>(rprob, rp, W, [&](int s, float(&w)[E]) {
+            chunk_weights<DT, ExpW>(rp, cp, nullptr, 0, s, w);
+        });
+}
+
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ float uniform(float v) { return as_f(__builtin_amdgcn_readfirstlane(as_i(v))); }
+
+// Path-only verification (Sec. 2: only the nodes the walk visits decide what a step emits): one
+// workgroup per tree starts at the root, verifies a node, and moves to the accepted child until
+// a node accepts nothing, a leaf has given its bonus token, or `depth` tokens are out.  Nodes
+// off the path keep outcome MDSD_UNVISITED.  verify_node(id) handles one node and returns its
+// outcome and token, uniform over the workgroup.
+template <class VerifyNode>
+__device__ __forceinline__ void walk_and_verify(const Params& P, VerifyNode verify_node)
+{
+    const int b = blockIdx.x;
+    for (int i = threadIdx.x; i < P.N; i += kWG) {
+        const int64_t r = (int64_t)b * P.N + i;
+        P.outcome[r] = MDSD_UNVISITED;
+        P.token[r] = -1;
+        if (P.flags) P.flags[r] = 0;
+        if (P.resid_mass) P.resid_mass[r] = 0.f;
+    }
+    int32_t* em = P.emitted + (int64_t)b * P.depth;
+    for (int i = threadIdx.x; i < P.depth; i += kWG) em[i] = -1;
+    // the visited nodes' entries are rewritten below by another thread of this workgroup
+    __threadfence_block();
+    __syncthreads();
+    int n = 0, d = 0;
+    for (;;) {
+        NodeId id;
+        id.b = b;
+        id.n = n;
+        if (P.first_child) {
+            id.c0 = P.first_child[n];
+            if (id.c0 < 1 || id.c0 + P.k > P.N) id.c0 = -1;
+        } else {
+            const int64_t c = (int64_t)P.k * n + 1;
+            id.c0 = (c + P.k <= P.N) ? (int)c : -1;
+        }
+        id.row = (int64_t)b * P.N + n;
+        const NodeOut o = verify_node(id);
+        const int outcome = uniform(o.outcome), token = uniform(o.token);
+        if (threadIdx.x == 0 && d < P.depth) em[d] = token;
+        if (id.c0 < 0 || outcome < 0 || outcome >= P.k || d + 1 >= P.depth) break;
+        n = id.c0 + outcome;
+        ++d;
+        __syncthreads();  // the next node reuses the LDS areas of this one
+    }
+    if (threadIdx.x == 0) P.accept_depth[b] = d;
+}
+
+// One sweep over a logit row that is streamed from memory (too long for registers), instead of
+// a pass for the maximum and a pass for the weights.  Each wave forms its weights against a
+// reference of its own, the largest element of its first slab; when the row's maximum M is
+// known the partial sums are brought to the row's units by one factor per wave,
+// 2^((reference - M) s) <= 1.  Returns false (caller falls back to two passes) when the sum
+// came out zero or not finite: some later element lay too far above a wave's reference.
+// On success: M = maximum of the stored row, Z = sum of 2^((l - M) s); with SLABS the slab
+// sums in LDS are in the same units and visible to every wave.
+template <int DT, bool SLABS, class Src>
+__device__ __forceinline__ bool sweep_streamed_row(const Src& src, float s, Shared& sh, int& phase, float& M,
+                                                   float& Z, float* lane_max_out = nullptr)
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    const int lane = threadIdx.x & 63, wave = wave_id();
+    const float ninf = -__builtin_inff();
+    float a0[E];
+    load_chunk<DT>(src.r, wave * 64 + lane, ninf, a0);  // slabs past the row read as -inf
+    float r = a0[0];
+#pragma unroll
+    for (int e = 1; e < E; ++e) r = fmaxf(r, a0[e]);
+    r = wave_max(r);
+    if (!(r > ninf) || !(r < __builtin_inff())) r = 0.f;  // nothing finite to refer to
+    ToWeight<true> cw;
+    cw.s = s;
+    cw.ms = uniform(r * s);
+    float lane_m = ninf, lane_z = 0.f;
+    src.for_each([&](int sl, int, const float(&a)[E]) {
+        float w[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            lane_m = fmaxf(lane_m, a[e]);
+            w[e] = cw(a[e]);
+        }
+        const float cs = chunk_sum<E>(w);
+        lane_z += cs;
+        if constexpr (SLABS) store_slab_sum(sh.slab_w, sl, cs);
+    });
+    if (lane_max_out) *lane_max_out = lane_m;
+    float mm[1] = {lane_m};
+    block_max<kWaves, 1>(mm, sh.red, phase);
+    M = mm[0];
+    const float scale = uniform(__builtin_amdgcn_exp2f(fmaf(r, s, -(M * s))));
+    float zz[1] = {lane_z * scale};
+    block_sum<kWaves, 1>(zz, sh.red, phase);  // barrier: every slab sum is stored
+    Z = zz[0];
+    const bool ok = Z > 0.f && Z < __builtin_inff();
+    if constexpr (SLABS) {
+        if (ok) {
+            for (int i = wave + kWaves * lane; i < src.r.nslab; i += kWaves * 64) sh.slab_w[i] *= scale;
+        }
+        __syncthreads();
+    }
+    return ok;
+}
+
+}  // namespace mdsd

@@ -1,0 +1,294 @@
+// RRS and RRS without replacement (Alg. 1) for logit rows that fit in registers.
+#include "launch.h"
+
+namespace mdsd {
+
+// ---------------------------------------------------------------- RRS / RRSw, rows in registers
+// Alg. 1 for one internal node when the draft call left its record of the draft row (largest
+// stored element, total mass): the target row sits in registers, the draft row is streamed once
+// per rejected round, and a node whose first draft is accepted never reads it.  The state after
+// i rejections is the residual U = max(p - c q, 0) with mass W (c_1 = 0, W_0 = 1,
+// c_{i+1} = c_i + W_i rho_{i+1}): round i + 1 accepts x with probability U(x) / (W q_{i+1}(x)).
+// WO (without replacement): q_{i+1} is q without the tokens rejected so far, rescaled by
+// rho_{i+1} = (mass of q) / (mass left); the mass outside all k drafted tokens is summed (positive
+// terms only) in the first pass over the draft row, the masses left are that plus the later drafts'.
+template <int DT, int NIT, bool MASKED, bool WO>
+__device__ __forceinline__ void rrs_resident(const Params& P, const NodeId& id, const RowView& rp,
+                                             const RowView& rq, const RowSrc<DT, NIT, MASKED>& sp,
+                                             bool need_full, float* rprob, Shared& sh, int& phase, NodeOut& o)
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    constexpr int HE = E / 2;
+    using Src = RowSrc<DT, NIT, MASKED>;
+    const int k = P.k;
+    const float* ur = P.u + id.row * (k + 1);
+    const int32_t* xt = P.tokens + (int64_t)id.b * P.N + id.c0;
+    const mdsd_row_stats st = P.stats_in[id.row];
+    // tokens, the stored logits at them and the uniforms go through LDS (lane i of the first wave
+    // fetches draft i), so that no lane holds arrays of them; visible after the first barrier
+    if ((int)threadIdx.x < k) {
+        const int i = threadIdx.x;
+        const int x = xt[i];
+        const bool ok = x >= 0 && x < P.V;
+        sh.node_x[i] = ok ? x : -1;
+        sh.node_lp[i] = ok ? load_elem<DT>(rp, x) : 0.f;
+        sh.node_lq[i] = ok ? load_elem<DT>(rq, x) : 0.f;
+        sh.node_u[i] = ur[i];
+    }
+    if (threadIdx.x == 0) sh.node_u[k] = ur[k];
+
+    // ---- target row: shift (cheap estimate first, where there is one) and Zp
+    ExpW cp, cq;
+    cp.s = kLog2e / P.temp_target;
+    cq.s = kLog2e / P.temp_draft;
+    cq.ms = uniform(st.max_stored * cq.s);
+    float z1[1];
+    auto normaliser = [&](float lane_m) {
+        float m1[1] = {lane_m};
+        block_max<kWaves, 1>(m1, sh.red, phase);
+        cp.ms = uniform(m1[0] * cp.s);
+        z1[0] = 0.f;
+        sp.for_each([&](int, int, const float(&pa_)[E]) {
+            float wp[E];
+#pragma unroll
+            for (int e = 0; e < E; ++e) wp[e] = cp(pa_[e]);
+            z1[0] += chunk_sum<E>(wp);
+        });
+        block_sum<kWaves, 1>(z1, sh.red, phase);
+    };
+    if constexpr (Src::kHasShiftEstimate) {
+        normaliser(sp.lane_shift_estimate());
+        if (__builtin_expect(!(z1[0] > 0.f && z1[0] < __builtin_inff()), 0)) normaliser(lane_max(sp));
+    } else {
+        normaliser(lane_max(sp));
+    }
+    const float iZp = uniform(1.f / z1[0]);
+    const float iZq = uniform(1.f / st.rest_mass);
+    bool bad = false;
+    for (int i = 0; i < k; ++i) bad = bad || sh.node_x[i] < 0;
+    if (bad) {
+        o.flags |= MDSD_FLAG_BAD_TOKEN;
+        o.outcome = MDSD_BAD_TOKEN;
+        return;
+    }
+    const float u_last = sh.node_u[k];
+
+    float c = 0.f, Wc = 1.f;
+    bool decided = false, slabs_current = false;
+    int n_rej = 0;
+    float rem_k = 0.f;  // WO: unnormalised draft mass outside all k drafted tokens (after the first pass)
+    // one pass over both rows: slab sums (and total) of max(p - c_new q, 0), rejected tokens masked;
+    // with want_rem also the draft mass outside the drafted tokens
+    auto residual_pass = [&](float c_new, bool want_rem) {
+        const float c_iZq = c_new * iZq;
+        // slabs of the first two tokens to mask (with more than two, every slab takes the slow check)
+        const int n_mask = want_rem ? k : n_rej;
+        const int s_lo = (sh.node_x[0] + rp.head) / (64 * E);
+        const int s_hi = n_mask > 1 ? (sh.node_x[1] + rp.head) / (64 * E) : s_lo;
+        float lane_rem = 0.f;
+        SlabSums<NIT> sums;
+        // Opaque copies: the weights of the target row do not change from round to round, and
+        // the compiler would otherwise compute all of them once, ahead of the rounds, and hold
+        // one register per element.
+        int lane_o = threadIdx.x & 63, wave_o = wave_id();
+        ExpW cpo = cp;
+        asm volatile("" : "+v"(lane_o), "+s"(wave_o), "+s"(cpo.ms));
+        for_each_streamed_at<kStreamAhead>(lane_o, wave_o, sp, rq, ExpW::fill(), [&](int it, int s, int chunk, const uint4& dp, const uint4& dq) {
+            float part[2];
+            auto half = [&](auto H) {
+                constexpr int hv = decltype(H)::value;
+                float ep[HE], eq[HE], w[HE];
+                unpack_half<DT, MASKED, hv>(dp, rp, ExpW::fill(), chunk, ep);
+                unpack_half<DT, MASKED, hv>(dq, rq, ExpW::fill(), chunk, eq);
+#pragma unroll
+                for (int e = 0; e < HE; ++e) {
+                    eq[e] = cq(eq[e]);
+                    w[e] = rrs_term(cpo(ep[e]), eq[e], iZp, c_iZq);
+                }
+                if (__builtin_expect(s == s_lo || s == s_hi || n_mask > 2, 0)) {
+                    asm volatile("" ::: "memory");
+                    for (int j = 0; j < n_mask; ++j) {
+                        const int xvj = sh.node_x[j] + rp.head;
+#pragma unroll
+                        for (int e = 0; e < HE; ++e) {
+                            if (chunk * E + hv * HE + e == xvj) {
+                                if (j < n_rej) w[e] = 0.f;
+                                eq[e] = 0.f;  // only summed with want_rem, where every drafted token is left out
+                            }
+                        }
+                    }
+                }
+                if constexpr (HE == 4)
+                    part[hv] = (w[0] + w[1]) + (w[2] + w[3]);
+                else
+                    part[hv] = w[0] + w[1];
+                if constexpr (WO) {
+                    if (want_rem) {
+                        if constexpr (HE == 4)
+                            lane_rem += (eq[0] + eq[1]) + (eq[2] + eq[3]);
+                        else
+                            lane_rem += eq[0] + eq[1];
+                    }
+                }
+            };
+            half(std::integral_constant<int, 0>{});
+            __builtin_amdgcn_sched_barrier(0);
+            half(std::integral_constant<int, 1>{});
+            sums.put(it, part[0] + part[1]);
+        });
+        sums.store(sh.slab_w, rp.nslab);
+        if constexpr (WO) {
+            if (want_rem) {
+                float rr[1] = {lane_rem};
+                block_sum<kWaves, 1>(rr, sh.red, phase);
+                rem_k = rr[0];
+            }
+        }
+        __syncthreads();
+        return slab_total(rp.nslab, [&](int j) { return sh.slab_w[j]; });
+    };
+    // WO: unnormalised draft mass left before round i (i >= 1): what no draft took, plus the
+    // drafts still to come (a repeated token counts once)
+    auto mass_left = [&](int i) {
+        float m = rem_k;
+        for (int j = k - 1; j >= i; --j) {
+            bool dup = false;
+            for (int l = 0; l < j; ++l) dup = dup || (sh.node_x[l] == sh.node_x[j]);
+            if (!dup) m += cq(sh.node_lq[j]);
+        }
+        return m;
+    };
+
+    for (int i = 0; i < k; ++i) {
+        const int xi = uniform(sh.node_x[i]);
+        const float px = cp(sh.node_lp[i]) * iZp, qx = cq(sh.node_lq[i]) * iZq, ui = sh.node_u[i];
+        bool seen = false;
+        for (int j = 0; j < i; ++j) seen = seen || (sh.node_x[j] == xi);
+        const float Ux = seen ? 0.f : fmaxf(fmaf(-c, qx, px), 0.f);
+        // draft probability of x_i in this round and the factor that rescales q; without
+        // replacement a repeated token has no mass left
+        float Qi = qx, rho = 1.f;
+        if (WO && i > 0) {
+            const float left = mass_left(i);
+            Qi = seen ? 0.f : cq(sh.node_lq[i]) / left;
+            rho = 1.f / (left * iZq);
+        }
+        if (ui * Qi * Wc < Ux) {  // Alg. 1 returns at the first acceptance
+            o.outcome = i;
+            o.token = xi;
+            decided = true;
+            break;
+        }
+        const float c_new = fmaf(Wc, rho, c);
+        n_rej = i + 1;
+        if (i > 0) __syncthreads();  // earlier readers of the slab sums are done
+        const float W_new = residual_pass(c_new, WO && i == 0);
+        if (W_new > 0.f) {
+            c = c_new;
+            Wc = W_new;
+            slabs_current = true;
+        } else {
+            o.flags |= MDSD_FLAG_ZERO_RESIDUAL;
+            slabs_current = false;
+        }
+        if constexpr (WO) {
+            if (!(mass_left(i + 1) > 0.f)) {
+                o.flags |= MDSD_FLAG_Q_EXHAUSTED;
+                break;
+            }
+        }
+    }
+    if (decided && !need_full) return;
+    if (!slabs_current) {
+        __syncthreads();
+        residual_pass(c, false);
+    }
+    const float c_iZq = c * iZq;
+    auto cw = [&](int s, float(&w)[E]) {
+        rrs_chunk_w<DT, ExpW>(rp, rq, cp, cq, iZp, c_iZq, nullptr, 0, s, w);
+        const int chunk = s * 64 + (threadIdx.x & 63);
+        for (int j = 0; j < n_rej; ++j) {
+            const int off = sh.node_x[j] + rp.head - chunk * E;
+#pragma unroll
+            for (int e = 0; e < E; ++e) w[e] = (e == off) ? 0.f : w[e];
+        }
+    };
+    auto sv = [&](int j) { return sh.slab_w[j]; };
+    const float W = slab_total(rp.nslab, sv);
+    o.rmass = W;
+    if (!decided) {
+        const int v = icdf_slabs<E>(rp.nslab, u_last, W, sv, cw);
+        o.token = v < 0 ? -1 : v - rp.head;
+        if (v < 0) o.flags |= MDSD_FLAG_ZERO_RESIDUAL;
+    }
+    if (rprob) write_resid_prob<DT>(rprob, rp, W, cw);
+}
+
+template <int DT, int NIT, bool MASKED, bool WO>
+__device__ __forceinline__ NodeOut rrs_node_resident(const Params& P, const NodeId& id, Shared& sh, int& phase)
+{
+    const bool need_full = (P.resid_mass != nullptr) || (P.resid_prob != nullptr);
+    float* rprob = P.resid_prob ? P.resid_prob + id.row * (int64_t)P.V : nullptr;
+    const RowView rp = make_row<DT>(P.target, P.ld_t, id.row, P.V);
+    RowSrc<DT, NIT, MASKED> sp;
+    sp.issue(rp, ExpW::fill());
+    NodeOut o{MDSD_NONE, -1, 0, 0.f};
+    if (id.c0 < 0) {
+        leaf_resident<DT, NIT, MASKED>(P, rp, sp, P.u[id.row * (P.k + 1) + P.k], rprob, sh, phase, o);
+    } else {
+        const RowView rq = make_row<DT>(P.draft, P.ld_d, id.row, P.V);
+        rrs_resident<DT, NIT, MASKED, WO>(P, id, rp, rq, sp, need_full, rprob, sh, phase, o);
+    }
+    if (threadIdx.x == 0) {
+        P.outcome[id.row] = o.outcome;
+        P.token[id.row] = o.token;
+        if (P.resid_mass) P.resid_mass[id.row] = o.rmass;
+        if (P.flags) P.flags[id.row] = o.flags;
+    }
+    return o;
+}
+
+template <int DT, int NIT, bool MASKED, bool WO>
+__global__ __launch_bounds__(kWG, (NIT <= 8 ? kStatsWavesPerSimd : 2)) void rrs_verify_resident(const Params P)
+{
+    __shared__ Shared sh;
+    int phase = 0;
+    rrs_node_resident<DT, NIT, MASKED, WO>(P, node_of_block(P), sh, phase);
+}
+
+// which shapes the RRS kernel for rows in registers is built for (the others would spill or run
+// one workgroup per CU; they take the generic kernel): fp32 in every size, bf16 up to 8 chunks per
+// lane and only for rows that need no masking
+bool rrs_resident_covers(int dtype, int nit, bool masked)
+{
+    return nit > 0 && (dtype == MDSD_FP32 || (nit <= 8 && !masked));
+}
+template <bool WO>
+static void launch_rrs_resident_of(int dtype, int nit, bool masked, dim3 grid, dim3 block, hipStream_t st,
+                                const Params& P)
+{
+#define MDSD_LAUNCH_RRS(DT, N, M) hipLaunchKernelGGL((rrs_verify_resident<DT, N, M, WO>), grid, block, 0, st, P)
+    if (dtype == MDSD_FP32) {
+        if (nit == 4) {
+            if (masked) MDSD_LAUNCH_RRS(0, 4, true); else MDSD_LAUNCH_RRS(0, 4, false);
+        } else if (nit == 8) {
+            if (masked) MDSD_LAUNCH_RRS(0, 8, true); else MDSD_LAUNCH_RRS(0, 8, false);
+        } else {
+            if (masked) MDSD_LAUNCH_RRS(0, 16, true); else MDSD_LAUNCH_RRS(0, 16, false);
+        }
+    } else {
+        if (nit == 4) MDSD_LAUNCH_RRS(1, 4, false); else MDSD_LAUNCH_RRS(1, 8, false);
+    }
+#undef MDSD_LAUNCH_RRS
+}
+
+void launch_rrs_resident(bool without_replacement, int dtype, int nit, bool masked, dim3 grid, dim3 block,
+                         hipStream_t st, const Params& P)
+{
+    if (without_replacement)
+        launch_rrs_resident_of<true>(dtype, nit, masked, grid, block, st, P);
+    else
+        launch_rrs_resident_of<false>(dtype, nit, masked, grid, block, st, P);
+}
+
+}  // namespace mdsd
