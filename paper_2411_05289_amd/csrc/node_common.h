@@ -429,7 +429,8 @@ __device__ __forceinline__ void walk_and_verify(const Params& P, VerifyNode veri
 // reference of its own, the largest element of its first slab; when the row's maximum M is
 // known the partial sums are brought to the row's units by one factor per wave,
 // 2^((reference - M) s) <= 1.  Returns false (caller falls back to two passes) when the sum
-// came out zero or not finite: some later element lay too far above a wave's reference.
+// came out zero or not finite (some later element lay too far above a wave's reference) or a
+// wave's factor is below 2^-100.
 // On success: M = maximum of the stored row, Z = sum of 2^((l - M) s); with SLABS the slab
 // sums in LDS are in the same units and visible to every wave.
 template <int DT, bool SLABS, class Src>
@@ -465,8 +466,11 @@ __device__ __forceinline__ bool sweep_streamed_row(const Src& src, float s, Shar
     float mm[1] = {lane_m};
     block_max<kWaves, 1>(mm, sh.red, phase);
     M = mm[0];
-    const float scale = uniform(__builtin_amdgcn_exp2f(fmaf(r, s, -(M * s))));
-    float zz[1] = {lane_z * scale};
+    // A wave whose reference lies far below the maximum would scale its sums by a factor near
+    // or below the smallest normal number and lose them: then the sweep does not count.
+    const float down = fmaf(r, s, -(M * s));
+    const float scale = uniform(__builtin_amdgcn_exp2f(down));
+    float zz[1] = {down < -100.f ? __builtin_inff() : lane_z * scale};
     block_sum<kWaves, 1>(zz, sh.red, phase);  // barrier: every slab sum is stored
     Z = zz[0];
     const bool ok = Z > 0.f && Z < __builtin_inff();

@@ -339,12 +339,14 @@ def test_empty_batch(method):
     torch.cuda.synchronize()
 
 
-def test_draft_mass_below_the_fp32_range_is_flagged():
+@pytest.mark.parametrize("V,Bn", [(4104, 6), (40000, 3)], ids=["in_registers", "streamed"])
+def test_draft_mass_below_the_fp32_range_is_flagged(V, Bn):
     """Rows so peaked (temperature 0.03) that, once the dominant token is removed, what is left is
     below 2^-126 of it: the kernels' fp32 weights then hold no mass.  rrsw_draft repeats the token
     and flags the node, spechub_draft gives the pair (a, a) and flags it, both verifiers still
-    return a valid outcome; where the rest is inside the range the tokens are the oracle's."""
-    wl = W.config(2, device=DEV, B=6, V=4104, k=2, depth=3, seed=300)
+    return a valid outcome; where the rest is inside the range the tokens are the oracle's (on
+    streamed rows the one-sweep statistics must notice that they cannot hold such a row)."""
+    wl = W.config(2, device=DEV, B=Bn, V=V, k=2, depth=3, seed=300)
     wl.temp_target, wl.temp_draft = 0.02, 0.03
     pb = B.Problem.from_workload(wl)
     u_d, u_v = uniforms(wl, 300)
