@@ -263,9 +263,12 @@ __device__ __forceinline__ void for_each_streamed_at(int lane, int wave, const R
     static_assert(NIT > 0 && QW > 0, "row a must be resident");
     const uint32_t fb = __builtin_bit_cast(uint32_t, fill_b);
     const uint32_t fw = DT == 0 ? fb : ((fb >> 16) | (fb & 0xffff0000u));
+    // Every lane issues every load (a lane past the row reads the row's last chunk again and
+    // drops it below): with a load inside a branch the compiler could not count the loads in
+    // flight and would wait for all of them, the one just issued included, before each use.
     auto fetch = [&](int it) {
         const int chunk = (it * kWaves + wave) * 64 + lane;
-        return chunk < rb.nchunk ? load16(rb.chunks, chunk) : make_uint4(fw, fw, fw, fw);
+        return load16(rb.chunks, chunk < rb.nchunk ? chunk : rb.nchunk - 1);
     };
     uint4 win[QW];
 #pragma unroll
@@ -273,9 +276,14 @@ __device__ __forceinline__ void for_each_streamed_at(int lane, int wave, const R
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
         const int s = it * kWaves + wave;
-        const uint4 cur = win[it % QW];
+        uint4 cur = win[it % QW];
         if (it + QW < NIT) win[it % QW] = fetch(it + QW);
-        if (s < sa.r.nslab) body(it, s, s * 64 + lane, sa.d[it], cur);
+        if (s < sa.r.nslab) {
+            if ((s + 1) * 64 > rb.nchunk) {  // the row's last slab, not full
+                if (s * 64 + lane >= rb.nchunk) cur = make_uint4(fw, fw, fw, fw);
+            }
+            body(it, s, s * 64 + lane, sa.d[it], cur);
+        }
         __builtin_amdgcn_sched_barrier(0);  // one chunk pair at a time
     }
 }
