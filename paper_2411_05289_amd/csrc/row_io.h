@@ -99,18 +99,16 @@ __device__ __forceinline__ void load_chunk(const RowView& r, int chunk, float fi
                                            float (&v)[Elem<DT>::kPerChunk])
 {
     constexpr int E = Elem<DT>::kPerChunk;
-    if (chunk < r.nchunk) {
-        const uint4 d = load16(r.chunks, chunk);
-        unpack<DT>(d, v);
-        const int v0 = chunk * E;
-        if (v0 < r.head || v0 + E > r.nvirt) {
+    // The load itself is unconditional (a chunk past the end reads the row's last chunk and is
+    // masked whole below): a load inside a branch is waited for inside it, so two rows read side
+    // by side would cost two trips to memory instead of one.
+    const uint4 d = load16(r.chunks, chunk < r.nchunk ? chunk : r.nchunk - 1);
+    unpack<DT>(d, v);
+    const int v0 = chunk * E;
+    if (v0 < r.head || v0 + E > r.nvirt) {
 #pragma unroll
-            for (int e = 0; e < E; ++e)
-                if (v0 + e < r.head || v0 + e >= r.nvirt) v[e] = fill;
-        }
-    } else {
-#pragma unroll
-        for (int e = 0; e < E; ++e) v[e] = fill;
+        for (int e = 0; e < E; ++e)
+            if (v0 + e < r.head || v0 + e >= r.nvirt) v[e] = fill;
     }
 }
 

@@ -43,21 +43,24 @@ __device__ __forceinline__ void fetch_node_scalars(const Params& P, const NodeId
     }
 }
 
-// then the stored logits at the tokens those loads named
+// then the stored logits at the tokens those loads named.  All of them are asked for at once,
+// at indices brought into the row (a look-up inside a branch would be waited for inside it, and
+// the next one would cost another trip to memory); what an unusable token read is dropped.
 template <int DT, bool STATS>
-__device__ __forceinline__ void fetch_node_lookups(const NodeId& id, const RowView& rp, const RowView& rq,
+__device__ __forceinline__ void fetch_node_lookups(const NodeId& id, int V, const RowView& rp, const RowView& rq,
                                                    NodeIn& in)
 {
     if (id.c0 >= 0) {
-        if (in.tokens_ok) {
-            in.lp1 = load_elem<DT>(rp, in.x1);
-            in.lq1 = load_elem<DT>(rq, in.x1);
-            in.lp2 = load_elem<DT>(rp, in.x2);
-            in.lq2 = load_elem<DT>(rq, in.x2);
-        }
-        if constexpr (STATS) {
-            if (in.hub >= 0) in.lpa = load_elem<DT>(rp, in.hub);
-        }
+        const int c1 = min(max(in.x1, 0), V - 1), c2 = min(max(in.x2, 0), V - 1);
+        const float lp1 = load_elem<DT>(rp, c1), lq1 = load_elem<DT>(rq, c1);
+        const float lp2 = load_elem<DT>(rp, c2), lq2 = load_elem<DT>(rq, c2);
+        float lpa = 0.f;
+        if constexpr (STATS) lpa = load_elem<DT>(rp, max(in.hub, 0));
+        in.lp1 = in.tokens_ok ? lp1 : 0.f;
+        in.lq1 = in.tokens_ok ? lq1 : 0.f;
+        in.lp2 = in.tokens_ok ? lp2 : 0.f;
+        in.lq2 = in.tokens_ok ? lq2 : 0.f;
+        if constexpr (STATS) in.lpa = in.hub >= 0 ? lpa : 0.f;
     }
 }
 
@@ -66,7 +69,7 @@ __device__ __forceinline__ void fetch_node_inputs(const Params& P, const NodeId&
                                                   const RowView& rq, NodeIn& in)
 {
     fetch_node_scalars<STATS>(P, id, in);
-    fetch_node_lookups<DT, STATS>(id, rp, rq, in);
+    fetch_node_lookups<DT, STATS>(id, P.V, rp, rq, in);
 }
 
 // internal node, SpecHub (Alg. 3)
