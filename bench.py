@@ -212,6 +212,29 @@ def main():
     kernel_ms = two_ms - one_ms
     event_overhead_ms = one_ms - kernel_ms
     achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
+    # Reference line: a plain device copy of the same target rows (the library's copy kernel,
+    # nothing of the method), timed the same way on the rotating copies: what a kernel that only
+    # moves bytes reaches on a buffer of this size (it reads and writes, so twice the bytes).
+    srcs = [w.target for w in wls]
+    dst = torch.empty_like(srcs[0])
+    for v in srcs:
+        dst.copy_(v)
+    r_one = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    r_two = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for i in range(reps):
+        a, b = srcs[(2 * i) % copies], srcs[(2 * i + 1) % copies]
+        r_one[i][0].record()
+        dst.copy_(a)
+        r_one[i][1].record()
+        r_two[i][0].record()
+        dst.copy_(b)
+        dst.copy_(a)
+        r_two[i][1].record()
+    torch.cuda.synchronize()
+    copy_ms = (sum(e0.elapsed_time(e1) for e0, e1 in r_two) - sum(e0.elapsed_time(e1) for e0, e1 in r_one)) / reps
+    copy_bytes = 2 * srcs[0].numel() * srcs[0].element_size()
+    plain_copy_gbs = copy_bytes / (copy_ms * 1e-3) / 1e9 if copy_ms > 0 else None
+    del dst
     tps = float(ad.float().mean().item()) + 1.0
     kernel_key = "%s_verify:%s" % (args.method, wl0.name)
     traffic = read_traffic(kernel_key)
@@ -233,7 +256,10 @@ def main():
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": kernel_ms,
                      "event_bracket_ms": bracket_ms, "event_overhead_ms": event_overhead_ms,
                      "traffic": traffic,
-                     "hbm_measured_gbs": None if traffic is None else traffic / (kernel_ms * 1e-3) / 1e9},
+                     "hbm_measured_gbs": None if traffic is None else traffic / (kernel_ms * 1e-3) / 1e9,
+                     "plain_copy_reference": {"gbs": plain_copy_gbs, "bytes": copy_bytes,
+                                              "what": "device copy of the target rows of one input copy, "
+                                                      "bytes read + written"}},
     }
     if not args.no_path_only:
         # the same step with verification restricted to the nodes the walk visits (the walk is
