@@ -93,16 +93,23 @@ __device__ __forceinline__ void unpack(const uint4& d, float (&v)[Elem<DT>::kPer
 }
 
 // Chunk `chunk` of the row as floats; chunks past the end read as `fill`,
-// masked elements of the first and last chunk are replaced by `fill`.
+// masked elements of the first and last chunk are replaced by `fill`.  In two steps, so that
+// a loop can ask for its next chunk before it works on the current one:
+// fetch_chunk queues the load, finish_chunk turns what arrived into floats.
+// The load itself is unconditional (a chunk past the end reads the row's last chunk and is
+// masked whole afterwards): a load inside a branch is waited for inside it, so two rows read
+// side by side would cost two trips to memory instead of one, and the compiler could not
+// count the loads in flight.
+__device__ __forceinline__ uint4 fetch_chunk(const RowView& r, int chunk)
+{
+    return load16(r.chunks, chunk < r.nchunk ? chunk : r.nchunk - 1);
+}
+
 template <int DT>
-__device__ __forceinline__ void load_chunk(const RowView& r, int chunk, float fill,
-                                           float (&v)[Elem<DT>::kPerChunk])
+__device__ __forceinline__ void finish_chunk(const RowView& r, int chunk, const uint4& d, float fill,
+                                             float (&v)[Elem<DT>::kPerChunk])
 {
     constexpr int E = Elem<DT>::kPerChunk;
-    // The load itself is unconditional (a chunk past the end reads the row's last chunk and is
-    // masked whole below): a load inside a branch is waited for inside it, so two rows read side
-    // by side would cost two trips to memory instead of one.
-    const uint4 d = load16(r.chunks, chunk < r.nchunk ? chunk : r.nchunk - 1);
     unpack<DT>(d, v);
     const int v0 = chunk * E;
     if (v0 < r.head || v0 + E > r.nvirt) {
@@ -110,6 +117,13 @@ __device__ __forceinline__ void load_chunk(const RowView& r, int chunk, float fi
         for (int e = 0; e < E; ++e)
             if (v0 + e < r.head || v0 + e >= r.nvirt) v[e] = fill;
     }
+}
+
+template <int DT>
+__device__ __forceinline__ void load_chunk(const RowView& r, int chunk, float fill,
+                                           float (&v)[Elem<DT>::kPerChunk])
+{
+    finish_chunk<DT>(r, chunk, fetch_chunk(r, chunk), fill, v);
 }
 
 }  // namespace mdsd

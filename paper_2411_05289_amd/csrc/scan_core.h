@@ -174,11 +174,16 @@ struct RowSrc<DT, 0, MASKED> {
     template <class Body>
     __device__ __forceinline__ void for_each(Body body) const
     {
+        // each chunk is asked for one step ahead of its use (the step past the end reads the
+        // row's last chunk again and drops it)
         const int lane = threadIdx.x & 63, wave = wave_id();
+        uint4 cur = fetch_chunk(r, wave * 64 + lane);
         for (int s = wave; s < r.nslab; s += kWaves) {
+            const uint4 nxt = fetch_chunk(r, (s + kWaves) * 64 + lane);
             float a[E];
-            load_chunk<DT>(r, s * 64 + lane, fill, a);
+            finish_chunk<DT>(r, s * 64 + lane, cur, fill, a);
             body(s, s * 64 + lane, a);
+            cur = nxt;
         }
     }
 };
@@ -191,11 +196,17 @@ __device__ __forceinline__ void for_each2(const RowSrc<DT, NIT, MASKED>& sa, con
     constexpr int E = Elem<DT>::kPerChunk;
     const int lane = threadIdx.x & 63, wave = wave_id();
     if constexpr (NIT == 0) {
+        // both rows one step ahead of their use
+        uint4 ca = fetch_chunk(sa.r, wave * 64 + lane), cb = fetch_chunk(sb.r, wave * 64 + lane);
         for (int s = wave; s < sa.r.nslab; s += kWaves) {
+            const uint4 na = fetch_chunk(sa.r, (s + kWaves) * 64 + lane);
+            const uint4 nb = fetch_chunk(sb.r, (s + kWaves) * 64 + lane);
             float a[E], b[E];
-            load_chunk<DT>(sa.r, s * 64 + lane, sa.fill, a);
-            load_chunk<DT>(sb.r, s * 64 + lane, sb.fill, b);
+            finish_chunk<DT>(sa.r, s * 64 + lane, ca, sa.fill, a);
+            finish_chunk<DT>(sb.r, s * 64 + lane, cb, sb.fill, b);
             body(s, s * 64 + lane, a, b);
+            ca = na;
+            cb = nb;
         }
     } else {
 #pragma unroll
