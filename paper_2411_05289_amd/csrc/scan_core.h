@@ -188,25 +188,37 @@ struct RowSrc<DT, 0, MASKED> {
     }
 };
 
-// body(slab, chunk, a[E], b[E]) over two rows with the same head and length
-template <int DT, int NIT, bool MASKED, class Body>
+// body(slab, chunk, a[E], b[E]) over two rows with the same head and length.  Streamed rows are
+// asked for AHEAD (1 or 2) steps before their use; the steps past the end read the rows' last
+// chunks again and drop them.
+template <int AHEAD = 1, int DT, int NIT, bool MASKED, class Body>
 __device__ __forceinline__ void for_each2(const RowSrc<DT, NIT, MASKED>& sa, const RowSrc<DT, NIT, MASKED>& sb,
                                           Body body)
 {
+    static_assert(AHEAD == 1 || AHEAD == 2, "one or two steps ahead");
     constexpr int E = Elem<DT>::kPerChunk;
     const int lane = threadIdx.x & 63, wave = wave_id();
     if constexpr (NIT == 0) {
-        // both rows one step ahead of their use
-        uint4 ca = fetch_chunk(sa.r, wave * 64 + lane), cb = fetch_chunk(sb.r, wave * 64 + lane);
+        uint4 ca[AHEAD], cb[AHEAD];
+#pragma unroll
+        for (int i = 0; i < AHEAD; ++i) {
+            ca[i] = fetch_chunk(sa.r, (wave + i * kWaves) * 64 + lane);
+            cb[i] = fetch_chunk(sb.r, (wave + i * kWaves) * 64 + lane);
+        }
         for (int s = wave; s < sa.r.nslab; s += kWaves) {
-            const uint4 na = fetch_chunk(sa.r, (s + kWaves) * 64 + lane);
-            const uint4 nb = fetch_chunk(sb.r, (s + kWaves) * 64 + lane);
+            const uint4 na = fetch_chunk(sa.r, (s + AHEAD * kWaves) * 64 + lane);
+            const uint4 nb = fetch_chunk(sb.r, (s + AHEAD * kWaves) * 64 + lane);
             float a[E], b[E];
-            finish_chunk<DT>(sa.r, s * 64 + lane, ca, sa.fill, a);
-            finish_chunk<DT>(sb.r, s * 64 + lane, cb, sb.fill, b);
+            finish_chunk<DT>(sa.r, s * 64 + lane, ca[0], sa.fill, a);
+            finish_chunk<DT>(sb.r, s * 64 + lane, cb[0], sb.fill, b);
             body(s, s * 64 + lane, a, b);
-            ca = na;
-            cb = nb;
+#pragma unroll
+            for (int i = 0; i + 1 < AHEAD; ++i) {
+                ca[i] = ca[i + 1];
+                cb[i] = cb[i + 1];
+            }
+            ca[AHEAD - 1] = na;
+            cb[AHEAD - 1] = nb;
         }
     } else {
 #pragma unroll

@@ -125,7 +125,7 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                 }
                 z[1] = st.rest_mass;
             } else {
-                for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
+                for_each2<2>(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
                     float wp[E], wq[E];
 #pragma unroll
                     for (int e = 0; e < E; ++e) {
@@ -220,7 +220,7 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                     // ---- residual sums: S_xa = sum Q'(.,a), S_ax = sum Q'(a,.), slab sums of p''
                     float sacc[2] = {0.f, 0.f};
                     need_q();
-                    for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
+                    for_each2<2>(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
                         float ep[E], eq[E], t_xa[E], t_ax[E], w[E];
 #pragma unroll
                         for (int e = 0; e < E; ++e) {
