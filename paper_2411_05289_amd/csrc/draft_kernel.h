@@ -43,7 +43,7 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
         // a streamed logit row: maximum, weights and slab sums in one sweep
         float Z, mq_lane;
         cq.s = kLog2e / P.temp_draft;
-        swept = sweep_streamed_row<DT, true>(sq, cq.s, sh, phase, mm[0], Z, &mq_lane);
+        swept = sweep_streamed_row<DT, true, 2>(sq, cq.s, sh, phase, mm[0], Z, &mq_lane);
         if (swept) {
             cq.ms = mm[0] * cq.s;
             if constexpr (METHOD == kSpecHub) a_virt = block_argmax(sq, mq_lane, mm[0], sh, phase);

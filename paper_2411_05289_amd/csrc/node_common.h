@@ -433,7 +433,7 @@ __device__ __forceinline__ void walk_and_verify(const Params& P, VerifyNode veri
 // wave's factor is below 2^-100.
 // On success: M = maximum of the stored row, Z = sum of 2^((l - M) s); with SLABS the slab
 // sums in LDS are in the same units and visible to every wave.
-template <int DT, bool SLABS, class Src>
+template <int DT, bool SLABS, int AHEAD = 1, class Src>
 __device__ __forceinline__ bool sweep_streamed_row(const Src& src, float s, Shared& sh, int& phase, float& M,
                                                    float& Z, float* lane_max_out = nullptr)
 {
@@ -451,7 +451,7 @@ __device__ __forceinline__ bool sweep_streamed_row(const Src& src, float s, Shar
     cw.s = s;
     cw.ms = uniform(r * s);
     float lane_m = ninf, lane_z = 0.f;
-    src.for_each([&](int sl, int, const float(&a)[E]) {
+    src.template for_each<AHEAD>([&](int sl, int, const float(&a)[E]) {
         float w[E];
 #pragma unroll
         for (int e = 0; e < E; ++e) {

@@ -171,19 +171,24 @@ struct RowSrc<DT, 0, MASKED> {
     }
     __device__ __forceinline__ void issue(const RowView& rv, float f) { init(rv, f); }
 
-    template <class Body>
+    template <int AHEAD = 1, class Body>
     __device__ __forceinline__ void for_each(Body body) const
     {
-        // each chunk is asked for one step ahead of its use (the step past the end reads the
-        // row's last chunk again and drops it)
+        // each chunk is asked for AHEAD steps before its use (the steps past the end read the
+        // row's last chunk again and drop it)
+        static_assert(AHEAD == 1 || AHEAD == 2, "one or two steps ahead");
         const int lane = threadIdx.x & 63, wave = wave_id();
-        uint4 cur = fetch_chunk(r, wave * 64 + lane);
+        uint4 c[AHEAD];
+#pragma unroll
+        for (int i = 0; i < AHEAD; ++i) c[i] = fetch_chunk(r, (wave + i * kWaves) * 64 + lane);
         for (int s = wave; s < r.nslab; s += kWaves) {
-            const uint4 nxt = fetch_chunk(r, (s + kWaves) * 64 + lane);
+            const uint4 nxt = fetch_chunk(r, (s + AHEAD * kWaves) * 64 + lane);
             float a[E];
-            finish_chunk<DT>(r, s * 64 + lane, cur, fill, a);
+            finish_chunk<DT>(r, s * 64 + lane, c[0], fill, a);
             body(s, s * 64 + lane, a);
-            cur = nxt;
+#pragma unroll
+            for (int i = 0; i + 1 < AHEAD; ++i) c[i] = c[i + 1];
+            c[AHEAD - 1] = nxt;
         }
     }
 };
