@@ -25,17 +25,33 @@ __device__ __forceinline__ void rrs_resident(const Params& P, const NodeId& id, 
     const int32_t* xt = P.tokens + (int64_t)id.b * P.N + id.c0;
     const mdsd_row_stats st = P.stats_in[id.row];
     // tokens, the stored logits at them and the uniforms go through LDS (lane i of the first wave
-    // fetches draft i), so that no lane holds arrays of them; visible after the first barrier
-    if ((int)threadIdx.x < k) {
-        const int i = threadIdx.x;
-        const int x = xt[i];
-        const bool ok = x >= 0 && x < P.V;
-        sh.node_x[i] = ok ? x : -1;
-        sh.node_lp[i] = ok ? load_elem<DT>(rp, x) : 0.f;
-        sh.node_lq[i] = ok ? load_elem<DT>(rq, x) : 0.f;
-        sh.node_u[i] = ur[i];
+    // fetches draft i), so that no lane holds arrays of them; visible after the first barrier.
+    // The tokens and uniforms come over the scalar path (their addresses are the same in every
+    // lane), so that waiting for a token does not wait for the row behind it; the look-ups at the
+    // tokens are then queued right behind the row, at indices brought into it, and arrive with it.
+    int x = -1;
+    float u_mine = 0.f;
+    for (int i = 0; i < k; ++i) {
+        const int xi = xt[i];
+        const float ui = ur[i];
+        if ((int)threadIdx.x == i) {
+            x = xi;
+            u_mine = ui;
+        }
     }
-    if (threadIdx.x == 0) sh.node_u[k] = ur[k];
+    const float u_k = ur[k];
+    {
+        const bool ok = x >= 0 && x < P.V;
+        const int xc = ok ? x : 0;
+        if ((int)threadIdx.x < k) {
+            const float lp = load_elem<DT>(rp, xc), lq = load_elem<DT>(rq, xc);
+            sh.node_x[threadIdx.x] = ok ? x : -1;
+            sh.node_lp[threadIdx.x] = ok ? lp : 0.f;
+            sh.node_lq[threadIdx.x] = ok ? lq : 0.f;
+            sh.node_u[threadIdx.x] = u_mine;
+        }
+    }
+    if (threadIdx.x == 0) sh.node_u[k] = u_k;
 
     // ---- target row: shift (cheap estimate first, where there is one) and Zp
     ExpW cp, cq;
