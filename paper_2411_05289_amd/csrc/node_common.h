@@ -330,6 +330,65 @@ __device__ __forceinline__ int draw_resident(int nslab, float u, float W, SlabVa
     return sh.bcast_i;
 }
 
+// Softmax statistics of a row in registers with one barrier instead of two.  Every wave shifts
+// by a maximum of its own (r_w, the largest of its lanes' values lane_m: their maxima, or the
+// cheap estimates of them) and sums its weights; after one barrier the waves' pairs (r_w, Z_w)
+// are combined: M = max r_w, Z = sum Z_w f_w with f_w = 2^((r_w - M) s) <= 1.  The factors are
+// formed from the rounded products r_w s themselves (the largest of them is the shift `ms` that
+// later passes use), so that a wave's weights times its factor are the weights those passes
+// compute, not merely close to them.  A wave far below the maximum contributes its true,
+// negligible share.  With SLABS the slab sums left in
+// LDS are in their wave's own units: slab i counts f_(i mod kWaves) times its stored value, and
+// f_lane is that factor for the slabs this lane reads in slab_total() and icdf_find_slab()
+// (slab = a multiple of 64 + lane).
+struct RowNorm {
+    float ms, Z, f_lane;  // ms = M s, the shift of 2^(l s - ms)
+};
+
+template <bool SLABS, class Src>
+__device__ __forceinline__ RowNorm wave_shifted_norm(const Src& sp, float s, float lane_m, Shared& sh, int& phase)
+{
+    static_assert((kWaves & (kWaves - 1)) == 0 && kWaves <= 64, "waves per workgroup: a power of two");
+    constexpr int E = Src::E;
+    const int lane = threadIdx.x & 63, wave = wave_id();
+    float r = wave_max(lane_m);
+    // a wave with nothing finite to refer to (its chunks lie past the row or hold -inf only)
+    // shifts by 0 and stays out of the maximum
+    const bool has_ref = r > -__builtin_inff() && r < __builtin_inff();
+    if (!has_ref) r = 0.f;
+    r = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, r)));
+    ToWeight<true> cw;
+    cw.s = s;
+    cw.ms = r * s;
+    float z = 0.f;
+    SlabSums<Src::kNit> sums;
+    sp.for_each_it([&](int it, int, int, const float(&a)[E]) {
+        float w[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) w[e] = cw(a[e]);
+        const float cs = chunk_sum<E>(w);
+        z += cs;
+        if constexpr (SLABS) sums.put(it, cs);
+    });
+    const float zw = wave_sum(z);
+    if (lane == 0) {
+        sh.red.buf[phase][wave][0] = has_ref ? cw.ms : -__builtin_inff();
+        sh.red.buf[phase][wave][1] = zw;
+    }
+    if constexpr (SLABS) sums.store(sh.slab_w, sp.r.nslab);
+    __syncthreads();
+    float ms = sh.red.buf[phase][0][0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) ms = fmaxf(ms, sh.red.buf[phase][w][0]);
+    float Z = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w)
+        Z += sh.red.buf[phase][w][1] * __builtin_amdgcn_exp2f(sh.red.buf[phase][w][0] - ms);
+    const float f_lane = __builtin_amdgcn_exp2f(sh.red.buf[phase][lane & (kWaves - 1)][0] - ms);
+    phase ^= 1;
+    return RowNorm{ms, Z, f_lane};
+}
+
 // leaf: bonus token ~ p (the k = 0 case of Alg. 1)
 template <int DT, int NIT, bool MASKED>
 __device__ __forceinline__ void leaf_resident(const Params& P, const RowView& rp,
@@ -340,16 +399,15 @@ __device__ __forceinline__ void leaf_resident(const Params& P, const RowView& rp
     using Src = RowSrc<DT, NIT, MASKED>;
     ExpW cp;
     cp.s = kLog2e / P.temp_target;
-    auto sv = [&](int i) { return sh.slab_w[i]; };
+    float f_lane = 1.f;
+    auto sv = [&](int i) { return sh.slab_w[i] * f_lane; };  // i = a multiple of 64 + lane
     float W;
     // the cheap estimate of the maximum as the shift where there is one; if the weights
     // overflowed or vanished with it, once more with the maximum itself
     auto slab_sums = [&](float lane_m) {
-        float mm[1] = {lane_m};
-        block_max<kWaves, 1>(mm, sh.red, phase);
-        cp.ms = mm[0] * cp.s;
-        pass_weights_to_slabs<ExpW>(sp, cp, nullptr, 0, sh.slab_w);
-        __syncthreads();
+        const RowNorm n = wave_shifted_norm<true>(sp, cp.s, lane_m, sh, phase);
+        cp.ms = n.ms;
+        f_lane = n.f_lane;
         return slab_total(rp.nslab, sv);
     };
     if constexpr (Src::kHasShiftEstimate) {

@@ -108,18 +108,9 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
         cq.ms = mm[1] * cq.s;
         float z1[1];
         auto normaliser = [&](float lane_m) {
-            float m1[1] = {lane_m};
-            block_max<kWaves, 1>(m1, sh.red, phase);
-            mm[0] = m1[0];
-            cp.ms = mm[0] * cp.s;
-            z1[0] = 0.f;
-            sp.for_each([&](int, int, const float(&pa_)[E]) {
-                float wp[E];
-#pragma unroll
-                for (int e = 0; e < E; ++e) wp[e] = cp(pa_[e]);
-                z1[0] += chunk_sum<E>(wp);
-            });
-            block_sum<kWaves, 1>(z1, sh.red, phase);
+            const RowNorm n = wave_shifted_norm<false>(sp, cp.s, lane_m, sh, phase);
+            cp.ms = n.ms;
+            z1[0] = n.Z;
         };
         if constexpr (Src::kHasShiftEstimate) {
             normaliser(sp.lane_shift_estimate());
