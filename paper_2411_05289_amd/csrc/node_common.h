@@ -526,7 +526,9 @@ __device__ __forceinline__ bool sweep_streamed_row(const Src& src, float s, Shar
     M = mm[0];
     // A wave whose reference lies far below the maximum would scale its sums by a factor near
     // or below the smallest normal number and lose them: then the sweep does not count.
-    const float down = fmaf(r, s, -(M * s));
+    // (formed from the rounded shifts, so that a wave's weights times its factor are the weights
+    // a later pass computes with the shift M s, bit for bit)
+    const float down = cw.ms - M * s;
     const float scale = uniform(__builtin_amdgcn_exp2f(down));
     float zz[1] = {down < -100.f ? __builtin_inff() : lane_z * scale};
     block_sum<kWaves, 1>(zz, sh.red, phase);  // barrier: every slab sum is stored
