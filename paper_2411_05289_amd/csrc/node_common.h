@@ -389,8 +389,11 @@ __device__ __forceinline__ RowNorm wave_shifted_norm(const Src& sp, float s, flo
     return RowNorm{ms, Z, f_lane};
 }
 
-// leaf: bonus token ~ p (the k = 0 case of Alg. 1)
-template <int DT, int NIT, bool MASKED>
+// leaf: bonus token ~ p (the k = 0 case of Alg. 1).
+// EVERY_WAVE = false: only the first wave's copy of `o` is complete (the caller's first thread
+// writes the node's outputs): the search for the drawn slab and inside it is then left to that
+// wave, which reads the slab's chunk from memory, instead of being repeated by all eight.
+template <int DT, int NIT, bool MASKED, bool EVERY_WAVE = true>
 __device__ __forceinline__ void leaf_resident(const Params& P, const RowView& rp,
                                               const RowSrc<DT, NIT, MASKED>& sp, float u, float* rprob,
                                               Shared& sh, int& phase, NodeOut& o)
@@ -419,12 +422,19 @@ __device__ __forceinline__ void leaf_resident(const Params& P, const RowView& rp
     } else {
         W = slab_sums(lane_max(sp));
     }
-    const int v = draw_resident<E>(rp.nslab, u, W, sv, [&](int it, float(&w)[E]) {
-        float a[E];
-        get_dyn(sp, it, a);
+    int v = -1;
+    if constexpr (EVERY_WAVE) {
+        v = draw_resident<E>(rp.nslab, u, W, sv, [&](int it, float(&w)[E]) {
+            float a[E];
+            get_dyn(sp, it, a);
 #pragma unroll
-        for (int e = 0; e < E; ++e) w[e] = cp(a[e]);
-    }, sh);
+            for (int e = 0; e < E; ++e) w[e] = cp(a[e]);
+        }, sh);
+    } else if (wave_id() == 0) {
+        v = icdf_slabs<E>(rp.nslab, u, W, sv, [&](int s, float(&w)[E]) {
+            chunk_weights<DT, ExpW>(rp, cp, nullptr, 0, s, w);
+        });
+    }
     o.token = v < 0 ? -1 : v - rp.head;
     if (v < 0) o.flags |= MDSD_FLAG_ZERO_RESIDUAL;
     o.rmass = 1.f;

@@ -225,7 +225,9 @@ __device__ __forceinline__ void rrs_resident(const Params& P, const NodeId& id, 
     const float W = slab_total(rp.nslab, sv);
     o.rmass = W;
     if (!decided) {
-        const int v = icdf_slabs<E>(rp.nslab, u_last, W, sv, cw);
+        // (the kernel's first thread writes the outputs: the first wave's draw is the one that counts)
+        int v = -1;
+        if (wave_id() == 0) v = icdf_slabs<E>(rp.nslab, u_last, W, sv, cw);
         o.token = v < 0 ? -1 : v - rp.head;
         if (v < 0) o.flags |= MDSD_FLAG_ZERO_RESIDUAL;
     }
@@ -242,7 +244,7 @@ __device__ __forceinline__ NodeOut rrs_node_resident(const Params& P, const Node
     sp.issue(rp, ExpW::fill());
     NodeOut o{MDSD_NONE, -1, 0, 0.f};
     if (id.c0 < 0) {
-        leaf_resident<DT, NIT, MASKED>(P, rp, sp, P.u[id.row * (P.k + 1) + P.k], rprob, sh, phase, o);
+        leaf_resident<DT, NIT, MASKED, false>(P, rp, sp, P.u[id.row * (P.k + 1) + P.k], rprob, sh, phase, o);
     } else {
         const RowView rq = make_row<DT>(P.draft, P.ld_d, id.row, P.V);
         rrs_resident<DT, NIT, MASKED, WO>(P, id, rp, rq, sp, need_full, rprob, sh, phase, o);

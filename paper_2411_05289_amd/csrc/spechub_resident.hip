@@ -76,7 +76,9 @@ __device__ __forceinline__ void fetch_node_inputs(const Params& P, const NodeId&
 // STATS: the hub and the draft row's normalisers come with the node (the draft call left
 // them); the draft row is then only needed for the residual sums, and is asked for only once
 // the first test has failed.
-template <int DT, int NIT, bool MASKED, bool STATS>
+// EVERY_WAVE = false: only the first wave's copy of `o` is complete (the caller's first thread
+// writes the node's outputs), and the final draw is left to that wave.
+template <int DT, int NIT, bool MASKED, bool STATS, bool EVERY_WAVE = true>
 __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& in, const RowView& rp,
                                                  const RowView& rq, const RowSrc<DT, NIT, MASKED>& sp,
                                                  RowSrc<DT, NIT, MASKED>& sq, bool need_full,
@@ -328,12 +330,15 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
     bool wrote_prob = false;
     if (!decided) {
         int v;
-        if constexpr (STATS)
-            // the drawn slab's share of the draft row comes from memory a second time (1 KiB)
-            v = icdf_slabs<E>(rp.nslab, u2, W, sv, [&](int s, float(&w)[E]) {
-                spechub_chunk_w<DT, ExpW>(rp, rq, cp, cq, h, a_virt, s, w);
-            });
-        else
+        if constexpr (STATS) {
+            // the drawn slab's share of both rows comes from memory a second time (2 KiB); W is
+            // the same in every wave, so is the choice between the draw and the fall-back below
+            v = -1;
+            if (W > 0.f && (EVERY_WAVE || wave == 0))
+                v = icdf_slabs<E>(rp.nslab, u2, W, sv, [&](int s, float(&w)[E]) {
+                    spechub_chunk_w<DT, ExpW>(rp, rq, cp, cq, h, a_virt, s, w);
+                });
+        } else
             v = draw_resident<E>(rp.nslab, u2, W, sv, [&](int it, float(&w)[E]) {
             float a_[E], b_[E];
             get_dyn(sp, it, a_);
@@ -347,7 +352,7 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
                 spechub_terms(ep, eq, h, t0, t1, w[e]);
             }
         }, sh);
-        if (v < 0) {
+        if (STATS ? !(W > 0.f) : v < 0) {
             // no residual mass: fall back to p itself
             o.flags |= MDSD_FLAG_ZERO_RESIDUAL;
             __syncthreads();
@@ -362,6 +367,7 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
                 wrote_prob = true;
             }
         }
+        if (v < 0) o.flags |= MDSD_FLAG_ZERO_RESIDUAL;
         o.token = v < 0 ? -1 : v - rp.head;
     }
     if (rprob && !wrote_prob)
@@ -373,7 +379,7 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
 // One node of SpecHub verify for logit rows that fit in registers: every load of the node queued
 // before anything waits, all passes over the target row from registers.  Writes the node's
 // outputs and returns its outcome and token (the same values in every lane).
-template <int DT, int NIT, bool MASKED, bool STATS>
+template <int DT, int NIT, bool MASKED, bool STATS, bool EVERY_WAVE = true>
 __device__ __forceinline__ NodeOut spechub_node_resident(const Params& P, const NodeId& id, Shared& sh, int& phase)
 {
     const bool need_full = (P.resid_mass != nullptr) || (P.resid_prob != nullptr);
@@ -390,9 +396,9 @@ __device__ __forceinline__ NodeOut spechub_node_resident(const Params& P, const 
     fetch_node_inputs<DT, STATS>(P, id, rp, rq, in);
     NodeOut o{MDSD_NONE, -1, 0, 0.f};
     if (id.c0 < 0)
-        leaf_resident<DT, NIT, MASKED>(P, rp, sp, in.u2, rprob, sh, phase, o);
+        leaf_resident<DT, NIT, MASKED, EVERY_WAVE>(P, rp, sp, in.u2, rprob, sh, phase, o);
     else
-        spechub_resident<DT, NIT, MASKED, STATS>(P, in, rp, rq, sp, sq, need_full, rprob, sh, phase, o);
+        spechub_resident<DT, NIT, MASKED, STATS, EVERY_WAVE>(P, in, rp, rq, sp, sq, need_full, rprob, sh, phase, o);
     if (threadIdx.x == 0) {
         P.outcome[id.row] = o.outcome;
         P.token[id.row] = o.token;
@@ -408,7 +414,8 @@ __global__ __launch_bounds__(kWG, (NIT <= 8 ? (STATS ? kStatsWavesPerSimd : 4) :
 {
     __shared__ Shared sh;
     int phase = 0;
-    spechub_node_resident<DT, NIT, MASKED, STATS>(P, node_of_block(P), sh, phase);
+    // one node per workgroup: nobody but the thread that writes the outputs needs them
+    spechub_node_resident<DT, NIT, MASKED, STATS, false>(P, node_of_block(P), sh, phase);
 }
 
 template <int DT, int NIT, bool MASKED, bool STATS>
