@@ -42,7 +42,7 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
     if constexpr (LOGITS && NIT == 0) {
         // a streamed logit row: maximum, weights and slab sums in one sweep
         float Z, mq_lane;
-        cq.s = kLog2e / P.temp_draft;
+        cq.s = P.scale_d;
         swept = sweep_streamed_row<DT, true, 2>(sq, cq.s, sh, phase, mm[0], Z, &mq_lane);
         if (swept) {
             cq.ms = mm[0] * cq.s;
@@ -56,7 +56,7 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
             block_max<kWaves, 1>(mm, sh.red, phase);
             if constexpr (METHOD == kSpecHub) a_virt = block_argmax(sq, mq_lane, mm[0], sh, phase);
             if constexpr (LOGITS) {
-                cq.s = kLog2e / P.temp_draft;
+                cq.s = P.scale_d;
                 cq.ms = mm[0] * cq.s;
             }
         }

@@ -124,6 +124,8 @@ static int validate(const mdsd_problem* pb, int method, bool need_target, Params
     P->ld_d = pb->ld_d;
     P->temp_target = pb->temp_target;
     P->temp_draft = pb->temp_draft;
+    P->scale_t = pb->kind == MDSD_LOGITS && need_target ? kLog2e / pb->temp_target : 0.f;
+    P->scale_d = pb->kind == MDSD_LOGITS ? kLog2e / pb->temp_draft : 0.f;
     P->B = pb->B;
     P->N = pb->N;
     P->V = pb->V;

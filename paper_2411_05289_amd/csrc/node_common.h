@@ -41,6 +41,9 @@ struct Params {
     const void* draft;
     int64_t ld_t, ld_d;
     float temp_target, temp_draft;
+    // log2(e) / temperature, formed once on the host: the correctly rounded quotient, which the
+    // kernels would otherwise each compute again with a dozen instructions per wave
+    float scale_t, scale_d;
     int B, N, V, k, depth, n_internal;
     const int32_t* first_child;
     const int32_t* tokens;
@@ -401,7 +404,7 @@ __device__ __forceinline__ void leaf_resident(const Params& P, const RowView& rp
     constexpr int E = Elem<DT>::kPerChunk;
     using Src = RowSrc<DT, NIT, MASKED>;
     ExpW cp;
-    cp.s = kLog2e / P.temp_target;
+    cp.s = P.scale_t;
     float f_lane = 1.f;
     auto sv = [&](int i) { return sh.slab_w[i] * f_lane; };  // i = a multiple of 64 + lane
     float W;

@@ -55,8 +55,8 @@ __device__ __forceinline__ void rrs_resident(const Params& P, const NodeId& id, 
 
     // ---- target row: shift (cheap estimate first, where there is one) and Zp
     ExpW cp, cq;
-    cp.s = kLog2e / P.temp_target;
-    cq.s = kLog2e / P.temp_draft;
+    cp.s = P.scale_t;
+    cq.s = P.scale_d;
     cq.ms = uniform(st.max_stored * cq.s);
     float z1[1];
     auto normaliser = [&](float lane_m) {

@@ -93,8 +93,8 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
     float mm[2], z[2] = {0.f, 0.f};
     int a_virt;
     ExpW cp, cq;
-    cp.s = kLog2e / P.temp_target;
-    cq.s = kLog2e / P.temp_draft;
+    cp.s = P.scale_t;
+    cq.s = P.scale_d;
     float lp_hub;
     if constexpr (STATS) {
         if (in.hub < 0) {  // no usable record for this node

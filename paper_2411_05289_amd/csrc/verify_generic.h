@@ -33,7 +33,7 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
         bool swept = false;
         if constexpr (LOGITS && NIT == 0) {
             float M, Z;
-            cp.s = kLog2e / P.temp_target;
+            cp.s = P.scale_t;
             swept = sweep_streamed_row<DT, true>(sp, cp.s, sh, phase, M, Z);
             cp.ms = M * cp.s;
         }
@@ -41,7 +41,7 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
             if constexpr (LOGITS) {
                 float mm[1] = {lane_max(sp)};
                 block_max<kWaves, 1>(mm, sh.red, phase);
-                cp.s = kLog2e / P.temp_target;
+                cp.s = P.scale_t;
                 cp.ms = mm[0] * cp.s;
             }
             pass_weights_to_slabs<CV>(sp, cp, nullptr, 0, sh.slab_w);
@@ -86,7 +86,7 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                 mm[0] = 0.f;
                 if constexpr (LOGITS && NIT == 0) {
                     // maximum and Zp of the streamed target row in one sweep
-                    swept = sweep_streamed_row<DT, false>(sp, kLog2e / P.temp_target, sh, phase, mm[0], z[0]);
+                    swept = sweep_streamed_row<DT, false>(sp, P.scale_t, sh, phase, mm[0], z[0]);
                 }
                 if (!swept) {
                     float m1[1] = {LOGITS ? lane_max(sp) : 0.f};
@@ -105,9 +105,9 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
             }
             const int a = a_virt - rq.head;
             if constexpr (LOGITS) {
-                cp.s = kLog2e / P.temp_target;
+                cp.s = P.scale_t;
                 cp.ms = mm[0] * cp.s;
-                cq.s = kLog2e / P.temp_draft;
+                cq.s = P.scale_d;
                 cq.ms = mm[1] * cq.s;
             }
             const int a_slab = a_virt / (64 * E);
@@ -311,7 +311,7 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                     if (have_stats) {
                         mm[0] = 0.f;
                         if constexpr (NIT == 0)
-                            swept = sweep_streamed_row<DT, false>(sp, kLog2e / P.temp_target, sh, phase, mm[0], z[0]);
+                            swept = sweep_streamed_row<DT, false>(sp, P.scale_t, sh, phase, mm[0], z[0]);
                         if (!swept) {
                             float m1[1] = {lane_max(sp)};
                             block_max<kWaves, 1>(m1, sh.red, phase);
@@ -324,9 +324,9 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                         mm[1] = lane_max(sq);
                         block_max<kWaves, 2>(mm, sh.red, phase);
                     }
-                    cp.s = kLog2e / P.temp_target;
+                    cp.s = P.scale_t;
                     cp.ms = mm[0] * cp.s;
-                    cq.s = kLog2e / P.temp_draft;
+                    cq.s = P.scale_d;
                     cq.ms = mm[1] * cq.s;
                 }
                 // exclusion list (virtual indices) and duplicate marks

@@ -4,6 +4,7 @@
 // bit-reproducible from launch to launch.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <limits.h>
 
 namespace mdsd {
 
@@ -44,25 +45,31 @@ __device__ __forceinline__ float wave_scan_add(float v)
     return v;
 }
 
-__device__ __forceinline__ float wave_scan_max(float v)
-{
-    const float ninf = -__builtin_inff();
-    v = fmaxf(v, dpp<kRowShr1>(ninf, v));
-    v = fmaxf(v, dpp<kRowShr2>(ninf, v));
-    v = fmaxf(v, dpp<kRowShr4>(ninf, v));
-    v = fmaxf(v, dpp<kRowShr8>(ninf, v));
-    v = fmaxf(v, dpp<kRowBcast15, 0xa>(ninf, v));
-    v = fmaxf(v, dpp<kRowBcast31, 0xc>(ninf, v));
-    return v;
-}
-
 __device__ __forceinline__ float lane_bcast(float v, int lane)
 {
     return as_f(__builtin_amdgcn_readlane(as_i(v), lane));
 }
 
 __device__ __forceinline__ float wave_sum(float v) { return lane_bcast(wave_scan_add(v), 63); }
-__device__ __forceinline__ float wave_max(float v) { return lane_bcast(wave_scan_max(v), 63); }
+
+// Largest value of the wave (NaN counts above +inf: callers that may hold NaN check the
+// result).  Taken on the order-preserving integer image of the floats: an integer maximum
+// needs no quieting of its inputs, so each step is one instruction with the lane shift folded
+// into it, instead of four.
+__device__ __forceinline__ float wave_max(float v)
+{
+    int k = as_i(v);
+    k ^= (k >> 31) & 0x7fffffff;
+    k = max(k, __builtin_amdgcn_update_dpp(INT_MIN, k, kRowShr1, 0xf, 0xf, false));
+    k = max(k, __builtin_amdgcn_update_dpp(INT_MIN, k, kRowShr2, 0xf, 0xf, false));
+    k = max(k, __builtin_amdgcn_update_dpp(INT_MIN, k, kRowShr4, 0xf, 0xf, false));
+    k = max(k, __builtin_amdgcn_update_dpp(INT_MIN, k, kRowShr8, 0xf, 0xf, false));
+    k = max(k, __builtin_amdgcn_update_dpp(INT_MIN, k, kRowBcast15, 0xa, 0xf, false));
+    k = max(k, __builtin_amdgcn_update_dpp(INT_MIN, k, kRowBcast31, 0xc, 0xf, false));
+    k = __builtin_amdgcn_readlane(k, 63);
+    k ^= (k >> 31) & 0x7fffffff;
+    return as_f(k);
+}
 
 // Eight wave-wide sums for the price of about two: every lane passes eight values; on return
 // lane l holds the sum over all 64 lanes of value number (l & 7).  Three halving steps inside
@@ -134,7 +141,7 @@ __device__ __forceinline__ void block_max(float (&v)[NV], BlockScratch<WAVES>& s
     const int lane = threadIdx.x & 63, wave = wave_id();
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-        float t = wave_scan_max(v[i]);
+        const float t = wave_max(v[i]);
         if (lane == 63) s.buf[phase][wave][i] = t;
     }
     __syncthreads();
