@@ -156,10 +156,21 @@ static bool rows_need_mask(const mdsd_problem* pb)
     const uintptr_t at = (uintptr_t)pb->target, ad = (uintptr_t)pb->draft;
     return (at & 15) || (ad & 15) || ((pb->ld_t * es) & 15) || ((pb->ld_d * es) & 15) || (pb->V % (16 / es));
 }
+// One workgroup per node.  Complete trees with more than one node: (trees, nodes), which
+// node_of_block() reads without a division (a one-node tree keeps gridDim.y == 1, which is how the
+// kernels tell the two numberings apart; there the single node is node 0 of tree blockIdx.x
+// either way).  Explicit topologies, and trees of more nodes than a grid's second dimension
+// holds: one dimension.
+static dim3 node_grid(const Params& P)
+{
+    if (P.first_child == nullptr && P.N > 1 && P.N <= 65535) return dim3((unsigned)P.B, (unsigned)P.N);
+    return dim3((unsigned)(P.B * P.N));
+}
+
 // path == false: one workgroup per node.  path == true: one workgroup per tree.
 static void launch_verify(int method, const mdsd_problem* pb, const Params& P, bool path, hipStream_t st)
 {
-    const dim3 grid((unsigned)(path ? P.B : P.B * P.N)), block(kWG);
+    const dim3 grid = path ? dim3((unsigned)P.B) : node_grid(P), block(kWG);
     const bool lg = pb->kind == MDSD_LOGITS;
     int nit = resident_chunks(pb);
     if (method == kSpecHub && lg && nit > 0) {
@@ -186,7 +197,7 @@ static void launch_verify(int method, const mdsd_problem* pb, const Params& P, b
 
 static void launch_draft(int method, const mdsd_problem* pb, const Params& P, hipStream_t st)
 {
-    const dim3 grid((unsigned)(P.B * P.N)), block(kWG);
+    const dim3 grid = node_grid(P), block(kWG);
     const bool lg = pb->kind == MDSD_LOGITS;
     const int nit = resident_chunks(pb);
     const int es = pb->dtype == MDSD_FP32 ? 4 : 2;

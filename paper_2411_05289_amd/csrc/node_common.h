@@ -107,7 +107,24 @@ __device__ __forceinline__ NodeId node_of_item(const Params& P, int w)
     return id;
 }
 
-__device__ __forceinline__ NodeId node_of_block(const Params& P) { return node_of_item(P, blockIdx.x); }
+// Complete trees are launched on a grid of (trees, nodes): the node number is the slow index, so
+// the workgroups still start in the order "nodes with children first", and nothing has to be
+// divided to find the tree and the node.  Other launches number their workgroups in one
+// dimension (gridDim.y == 1) and take the division.
+__device__ __forceinline__ NodeId node_of_block(const Params& P)
+{
+    if (gridDim.y == 1) return node_of_item(P, blockIdx.x);
+    NodeId id;
+    // Workgroup i of a launch runs on XCD i mod 8, and with the tree as the fast index that would
+    // be the tree's number mod 8 for every node: trees whose nodes cost more than others' (a
+    // poorer draft model) would weigh on one XCD.  Node n of a group of 8 trees is handed round
+    // inside the group instead.
+    id.n = blockIdx.y;
+    id.b = (P.B & 7) == 0 ? (int)(blockIdx.x ^ (blockIdx.y & 7u)) : (int)blockIdx.x;
+    id.c0 = id.n < P.n_internal ? P.k * id.n + 1 : -1;
+    id.row = (int64_t)id.b * P.N + id.n;
+    return id;
+}
 
 // ---------------------------------------------------------------- passes
 // max of the stored values this lane holds
