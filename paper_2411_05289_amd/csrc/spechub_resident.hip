@@ -378,7 +378,8 @@ __device__ __forceinline__ void spechub_resident(const Params& P, const NodeIn& 
 
 // One node of SpecHub verify for logit rows that fit in registers: every load of the node queued
 // before anything waits, all passes over the target row from registers.  Writes the node's
-// outputs and returns its outcome and token (the same values in every lane).
+// outputs and returns its outcome and token (with EVERY_WAVE the same values in every lane;
+// without it only the first wave's copy is complete).
 template <int DT, int NIT, bool MASKED, bool STATS, bool EVERY_WAVE = true>
 __device__ __forceinline__ NodeOut spechub_node_resident(const Params& P, const NodeId& id, Shared& sh, int& phase)
 {
