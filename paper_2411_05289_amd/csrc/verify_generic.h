@@ -6,9 +6,10 @@
 
 namespace mdsd {
 
-// The softmax scales arrive in scalar registers.  The streamed passes of this kernel measured
-// 4 % slower with the scale as a scalar operand of their multiply-adds than with the scale in
-// a vector register (config 4), so it is moved there once.
+// The softmax scales arrive in scalar registers.  The streamed passes of the SpecHub form of this
+// kernel measured 4 % slower with the scale as a scalar operand of their multiply-adds than with
+// the scale in a vector register (config 4), so it is moved there once; the RRS forms have no
+// register to spare for it (one more would cost them a wave per SIMD) and keep the scalar.
 __device__ __forceinline__ float in_vgpr(float x)
 {
     asm volatile("" : "+v"(x));
@@ -42,7 +43,7 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
         bool swept = false;
         if constexpr (LOGITS && NIT == 0) {
             float M, Z;
-            cp.s = in_vgpr(P.scale_t);
+            cp.s = (METHOD == kSpecHub ? in_vgpr(P.scale_t) : P.scale_t);
             swept = sweep_streamed_row<DT, true>(sp, cp.s, sh, phase, M, Z);
             cp.ms = M * cp.s;
         }
@@ -50,7 +51,7 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
             if constexpr (LOGITS) {
                 float mm[1] = {lane_max(sp)};
                 block_max<kWaves, 1>(mm, sh.red, phase);
-                cp.s = in_vgpr(P.scale_t);
+                cp.s = (METHOD == kSpecHub ? in_vgpr(P.scale_t) : P.scale_t);
                 cp.ms = mm[0] * cp.s;
             }
             pass_weights_to_slabs<CV>(sp, cp, nullptr, 0, sh.slab_w);
@@ -320,7 +321,7 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                     if (have_stats) {
                         mm[0] = 0.f;
                         if constexpr (NIT == 0)
-                            swept = sweep_streamed_row<DT, false>(sp, in_vgpr(P.scale_t), sh, phase, mm[0], z[0]);
+                            swept = sweep_streamed_row<DT, false>(sp, P.scale_t, sh, phase, mm[0], z[0]);
                         if (!swept) {
                             float m1[1] = {lane_max(sp)};
                             block_max<kWaves, 1>(m1, sh.red, phase);
@@ -333,9 +334,9 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                         mm[1] = lane_max(sq);
                         block_max<kWaves, 2>(mm, sh.red, phase);
                     }
-                    cp.s = in_vgpr(P.scale_t);
+                    cp.s = P.scale_t;
                     cp.ms = mm[0] * cp.s;
-                    cq.s = in_vgpr(P.scale_d);
+                    cq.s = P.scale_d;
                     cq.ms = mm[1] * cq.s;
                 }
                 // exclusion list (virtual indices) and duplicate marks
