@@ -29,6 +29,15 @@
  *     2^d - 1 nodes"); the children of n are k*n+1 .. k*n+k.  Otherwise
  *     first_child[n] is the index of node n's first child (its k children are
  *     consecutive) or -1 for a leaf, and `depth` bounds the walk.
+ *     Preconditions on the table, which the library cannot check as a whole:
+ *     every node but the root is the child of exactly one node (child ranges
+ *     do not overlap), and children come after their parent (first_child[n]
+ *     > n).  Per entry the kernels and the walk apply one rule: an entry
+ *     that is <= n or leaves no room for k children (first_child[n] + k > N)
+ *     makes node n a leaf, so no access leaves the arrays and every walk
+ *     ends; with overlapping ranges each node is still verified on its own
+ *     rows, but which tokens a shared child stands for is the caller's
+ *     business.
  *   - Rows: element (b, n, x) of `target` lives at target[(b*N + n)*ld_t + x].
  *     dtype selects fp32 or bf16 storage.  kind = MDSD_PROBS: rows are
  *     probabilities and are used as given (no renormalisation); kind =
@@ -132,7 +141,9 @@ typedef struct mdsd_result {
     float* resid_mass;     /* device [B,N] or NULL: mass of the node's residual in units of p.
                               SpecHub: sum_x p''(x) (= 1 - total acceptance, whatever the tokens);
                               RRS/RRSw: mass of max(p - c q, 0) when the node returned, i.e. the
-                              probability mass the rejections so far left; leaf: sum p.
+                              probability mass the rejections so far left (the product of the
+                              rejected rounds' sums of max(p_i - q_i, 0) in Alg. 1; 1 when the
+                              first draft was accepted); leaf: sum p.
                               Non-NULL disables SpecHub's early exit.                          */
     int32_t* flags;        /* device [B,N] or NULL: MDSD_FLAG_* bits                           */
     float* resid_prob;     /* device [B,N,V] or NULL (diagnostic): SpecHub: norm(p''); RRS/RRSw:

@@ -7,6 +7,48 @@
 namespace mdsd {
 
 // ---------------------------------------------------------------- tree walk
+// Sec. 2: follow the accepted children from the root; every visited node emits its token; stop at
+// the first node without an accepted child.  A first_child entry that does not point past its own
+// node or leaves no room for k children inside the tree counts as a leaf, the rule the verify
+// kernels apply to the same table: node numbers grow along the walk, which therefore ends.
+__device__ __forceinline__ int walk_first_child(const int32_t* first_child, int n, int k, int N)
+{
+    if (first_child) {
+        const int c0 = first_child[n];
+        return (c0 <= n || c0 + k > N) ? -1 : c0;
+    }
+    const int64_t c = (int64_t)k * n + 1;
+    return (c + k <= N) ? (int)c : -1;
+}
+
+// Trees of at most 64 nodes: one wavefront per tree.  Lane n fetches node n's outcome, token and
+// first child, so the whole tree arrives in one trip to memory; the walk itself then runs on
+// registers (the node number is the same in every lane).
+__global__ __launch_bounds__(256) void tree_walk_wave_kernel(const int32_t* outcome, const int32_t* token, int B,
+                                                             int N, int k, int depth, const int32_t* first_child,
+                                                             int32_t* accept_depth, int32_t* emitted)
+{
+    const int lane = threadIdx.x & 63;
+    const int b = blockIdx.x * (blockDim.x / 64) + (int)(threadIdx.x / 64);
+    if (b >= B) return;
+    const bool in_tree = lane < N;
+    const int oc = in_tree ? outcome[(int64_t)b * N + lane] : -1;
+    const int tk = in_tree ? token[(int64_t)b * N + lane] : -1;
+    const int c0 = in_tree ? walk_first_child(first_child, lane, k, N) : -1;
+    int32_t* em = emitted + (int64_t)b * depth;
+    int n = 0, d = 0, mine = -1;  // lane d keeps the token emitted at depth d (d < 64)
+    for (;;) {
+        const int t = __shfl(tk, n, 64), o = __shfl(oc, n, 64), c = __shfl(c0, n, 64);
+        if (lane == d) mine = t;
+        if (c < 0 || o < 0 || o >= k || d + 1 >= depth || d + 1 >= 64) break;
+        n = c + o;  // < N: c + k <= N
+        ++d;
+    }
+    for (int i = lane; i < depth; i += 64) em[i] = i < 64 ? mine : -1;
+    if (lane == 0) accept_depth[b] = d;
+}
+
+// Larger trees: one thread per tree, node after node from memory.
 __global__ void tree_walk_kernel(const int32_t* outcome, const int32_t* token, int B, int N, int k,
                                  int depth, const int32_t* first_child, int32_t* accept_depth,
                                  int32_t* emitted)
@@ -20,17 +62,10 @@ __global__ void tree_walk_kernel(const int32_t* outcome, const int32_t* token, i
     int n = 0, d = 0;
     for (;;) {
         if (d < depth) em[d] = tk[n];
-        int c0;
-        if (first_child) {
-            c0 = first_child[n];
-        } else {
-            const int64_t c = (int64_t)k * n + 1;
-            c0 = (c + k <= N) ? (int)c : -1;
-        }
+        const int c0 = walk_first_child(first_child, n, k, N);
         const int o = oc[n];
         if (c0 < 0 || o < 0 || o >= k || d + 1 >= depth) break;
         n = c0 + o;
-        if (n >= N) break;
         ++d;
     }
     accept_depth[b] = d;
@@ -216,10 +251,17 @@ static void launch_draft(int method, const mdsd_problem* pb, const Params& P, hi
 static int walk(const mdsd_problem* pb, const int32_t* outcome, const int32_t* token,
                 int32_t* accept_depth, int32_t* emitted, hipStream_t st)
 {
-    const int threads = 64;
-    hipLaunchKernelGGL(tree_walk_kernel, dim3((pb->B + threads - 1) / threads), dim3(threads), 0, st,
-                       outcome, token, pb->B, pb->N, pb->k, pb->depth, pb->first_child, accept_depth,
-                       emitted);
+    if (pb->N <= 64) {
+        const int trees_per_block = 4;
+        hipLaunchKernelGGL(tree_walk_wave_kernel, dim3((pb->B + trees_per_block - 1) / trees_per_block),
+                           dim3(64 * trees_per_block), 0, st, outcome, token, pb->B, pb->N, pb->k, pb->depth,
+                           pb->first_child, accept_depth, emitted);
+    } else {
+        const int threads = 64;
+        hipLaunchKernelGGL(tree_walk_kernel, dim3((pb->B + threads - 1) / threads), dim3(threads), 0, st,
+                           outcome, token, pb->B, pb->N, pb->k, pb->depth, pb->first_child, accept_depth,
+                           emitted);
+    }
     return hipGetLastError() == hipSuccess ? MDSD_OK : MDSD_E_LAUNCH;
 }
 

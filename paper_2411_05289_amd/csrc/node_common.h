@@ -100,8 +100,9 @@ __device__ __forceinline__ NodeId node_of_item(const Params& P, int w)
         id.b = w / P.N;
         id.n = w - id.b * P.N;
         id.c0 = P.first_child[id.n];
-        // an entry that leaves no room for k children is treated as a leaf
-        if (id.c0 < 1 || id.c0 + P.k > P.N) id.c0 = -1;
+        // an entry that does not point past its own node, or leaves no room for k children, is
+        // treated as a leaf (the tree walk applies the same rule, so it always ends)
+        if (id.c0 <= id.n || id.c0 + P.k > P.N) id.c0 = -1;
     }
     id.row = (int64_t)id.b * P.N + id.n;
     return id;
@@ -372,9 +373,18 @@ __device__ __forceinline__ RowNorm wave_shifted_norm(const Src& sp, float s, flo
     constexpr int E = Src::E;
     const int lane = threadIdx.x & 63, wave = wave_id();
     float r = wave_max(lane_m);
-    // a wave with nothing finite to refer to (its chunks lie past the row or hold -inf only)
-    // shifts by 0 and stays out of the maximum
-    const bool has_ref = r > -__builtin_inff() && r < __builtin_inff();
+    bool has_ref = r > -__builtin_inff() && r < __builtin_inff();
+    // The cheap estimates can miss every finite element of a wave: a 32-bit word whose upper
+    // half is -inf reads as -inf or as a NaN (which the maximum drops) whatever its lower half
+    // holds, so a wave whose finite logits all sit at even indices (rows with most tokens masked)
+    // would have nothing to refer to although it holds mass.  Such a wave takes the exact
+    // maximum of its elements instead (a branch the whole wave takes together, rarely).
+    if (!has_ref) {
+        r = wave_max(lane_max(sp));
+        has_ref = r > -__builtin_inff() && r < __builtin_inff();
+    }
+    // a wave that really has nothing finite (its chunks lie past the row or hold -inf only)
+    // shifts by 0, sums to 0 and stays out of the maximum
     if (!has_ref) r = 0.f;
     r = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, r)));
     ToWeight<true> cw;
@@ -495,7 +505,7 @@ __device__ __forceinline__ void walk_and_verify(const Params& P, VerifyNode veri
         id.n = n;
         if (P.first_child) {
             id.c0 = P.first_child[n];
-            if (id.c0 < 1 || id.c0 + P.k > P.N) id.c0 = -1;
+            if (id.c0 <= n || id.c0 + P.k > P.N) id.c0 = -1;
         } else {
             const int64_t c = (int64_t)P.k * n + 1;
             id.c0 = (c + P.k <= P.N) ? (int)c : -1;
@@ -518,7 +528,8 @@ __device__ __forceinline__ void walk_and_verify(const Params& P, VerifyNode veri
 // known the partial sums are brought to the row's units by one factor per wave,
 // 2^((reference - M) s) <= 1.  Returns false (caller falls back to two passes) when the sum
 // came out zero or not finite (some later element lay too far above a wave's reference) or a
-// wave's factor is below 2^-100.
+// wave's factor is below 2^-100 or above 2^100 (the latter only for a wave whose first slab held
+// nothing finite, which refers to 0: its weights may then have lost their low bits).
 // On success: M = maximum of the stored row, Z = sum of 2^((l - M) s); with SLABS the slab
 // sums in LDS are in the same units and visible to every wave.
 template <int DT, bool SLABS, int AHEAD = 1, class Src>
@@ -560,7 +571,7 @@ __device__ __forceinline__ bool sweep_streamed_row(const Src& src, float s, Shar
     // a later pass computes with the shift M s, bit for bit)
     const float down = cw.ms - M * s;
     const float scale = uniform(__builtin_amdgcn_exp2f(down));
-    float zz[1] = {down < -100.f ? __builtin_inff() : lane_z * scale};
+    float zz[1] = {!(fabsf(down) <= 100.f) ? __builtin_inff() : lane_z * scale};
     block_sum<kWaves, 1>(zz, sh.red, phase);  // barrier: every slab sum is stored
     Z = zz[0];
     const bool ok = Z > 0.f && Z < __builtin_inff();

@@ -223,7 +223,7 @@ __device__ __forceinline__ void rrs_resident(const Params& P, const NodeId& id, 
     };
     auto sv = [&](int j) { return sh.slab_w[j]; };
     const float W = slab_total(rp.nslab, sv);
-    o.rmass = W;
+    o.rmass = n_rej == 0 ? 1.f : W;
     if (!decided) {
         // (the kernel's first thread writes the outputs: the first wave's draw is the one that counts)
         int v = -1;

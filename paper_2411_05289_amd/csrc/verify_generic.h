@@ -485,7 +485,9 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                     }
                     auto sv = [&](int j) { return sh.slab_w[j]; };
                     const float W = slab_total(rp.nslab, sv);
-                    rmass = W;
+                    // the mass the rejections took p down to: nothing rejected, nothing taken
+                    // (rows of probabilities are used as given and need not sum to 1)
+                    rmass = n_rej == 0 ? 1.f : W;
                     if (!decided) {
                         const int v = icdf_slabs<E>(rp.nslab, ur[k], W, sv, cw);
                         token = v < 0 ? -1 : v - rp.head;

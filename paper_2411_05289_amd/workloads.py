@@ -107,6 +107,26 @@ def llm_like_logits(B, N, V, *, logit_std, draft_noise_std, zipf_s=1.1, dtype=to
     return target, draft
 
 
+def topk_masked_logits(B, N, V, K, *, overlap=0.6, dtype=torch.bfloat16, seed=0, device="cpu"):
+    """Rows as a top-k / top-p filter leaves them: every logit is -inf except K tokens per row, at
+    random positions (even and odd indices alike).  The draft row keeps about `overlap` of the
+    target row's tokens and puts the rest of its K tokens elsewhere."""
+    g = torch.Generator().manual_seed(seed)
+    target = torch.full((B, N, V), float("-inf"), dtype=torch.float32)
+    draft = torch.full((B, N, V), float("-inf"), dtype=torch.float32)
+    for b in range(B):
+        for n in range(N):
+            perm = torch.randperm(V, generator=g)
+            keep_t = perm[:K]
+            n_common = max(1, min(K, int(round(overlap * K))))
+            keep_d = torch.cat([keep_t[:n_common], perm[K:2 * K - n_common]])
+            vals = 3.0 * torch.randn(K, generator=g)
+            target[b, n, keep_t] = vals
+            draft[b, n, keep_d[:n_common]] = vals[:n_common] + torch.randn(n_common, generator=g)
+            draft[b, n, keep_d[n_common:]] = 3.0 * torch.randn(K - n_common, generator=g)
+    return target.to(dtype).to(device), draft.to(dtype).to(device)
+
+
 def dirichlet_rows(B, N, V, *, alpha=0.3, mix=0.7, seed=0, device="cpu"):
     """p ~ Dirichlet(alpha); q = mix * p + (1 - mix) * Dirichlet(alpha); both
     renormalised in fp64, then rounded to fp32."""

@@ -18,6 +18,17 @@ from paper_2411_05289_amd.workloads import Workload, rows_as_numpy
 
 BAND = 1e-6
 RESID_MASS_ATOL = 5e-7
+# every check_case appends (method, workload, counts) here; tests/conftest.py prints the list in
+# pytest's terminal summary (shown under -q too) and writes it to gpurun_out/parity_report.jsonl
+REPORT = []
+
+
+def mismatch_allowance(near) -> float:
+    """Nodes that may differ from the oracle: only nodes the oracle marks as within the band of
+    a threshold can differ at all, and of those only a part (the two sides round differently at
+    a fraction of the near nodes, not at all of them)."""
+    return 2 + 0.25 * float(near.sum())
+
 METHODS = {"spechub": oracle.SPECHUB, "rrs": oracle.RRS, "rrsw": oracle.RRSW}
 DRAFT = {"spechub": B.spechub_draft, "rrs": B.rrs_draft, "rrsw": B.rrsw_draft}
 VERIFY = {"spechub": B.spechub_verify, "rrs": B.rrs_verify, "rrsw": B.rrsw_verify}
@@ -130,7 +141,7 @@ def check_case(method: str, wl: Workload, seed: int = 0, seqs=None, full_outputs
         g_s = VERIFY[method](pb_s, tokens, u_v, resid_mass=False, flags=True, walk=True)
         out["mismatch_in_band_stats"] = _compare_nodes(g_s, o_v, idx, near, "early-exit+stats", ctx)
         _compare_walk(wl, g_s, o_v, idx, near)
-        assert out["mismatch_in_band_stats"] <= 2 + 0.02 * near.size, out
+        assert out["mismatch_in_band_stats"] <= mismatch_allowance(near), out
         g_path_s = VERIFY_PATH[method](pb_s, tokens, u_v, resid_mass=False, flags=True, walk=True)
         _compare_path(wl, g_path_s, o_v, idx, near, "path+stats")
         if full_outputs:
@@ -140,12 +151,13 @@ def check_case(method: str, wl: Workload, seed: int = 0, seqs=None, full_outputs
             valid = _np(g_sf["outcome"][idx]) >= -1
             bad = valid & (np.abs(rm_g - o_v["resid_mass"]) > 1e-5 * np.abs(o_v["resid_mass"]) + RESID_MASS_ATOL)
             assert not bad.any(), "resid_mass (stats) off at %s" % (np.argwhere(bad)[:5],)
+    REPORT.append((method, wl.name, dict(out)))
     if report is not None:
         report.append((method, wl.name, out))
     # An inverse-CDF draw lands within 1e-6 of a token boundary whenever it hits a token of
     # probability < 2e-6, so on LLM-sized vocabularies a few percent of the draws are "near";
-    # the nodes where the two sides then really differ must stay a small fraction.
-    assert out["mismatch_in_band"] <= 2 + 0.02 * near.size, out
+    # the nodes where the two sides then really differ must stay a fraction of those.
+    assert out["mismatch_in_band"] <= mismatch_allowance(near), out
     return out
 
 
@@ -226,7 +238,7 @@ def _compare_nodes(g, o, idx, near, label, ctx=None):
     fl = _np(g["flags"][idx])
     assert ((fl == o["flags"]) | near).all(), "%s: flags differ" % label
     if ctx is not None:
-        for b, n in np.argwhere(differ & near)[:200]:
+        for b, n in np.argwhere(differ & near):
             if oc_g[b, n] != -1 or o["outcome"][b, n] != -1:
                 continue  # an accept test within the band: either decision is admissible
             w, u = _node_draw_weights(ctx, b, n)

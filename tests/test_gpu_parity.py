@@ -209,6 +209,68 @@ def test_largest_supported_vocabulary(method, request):
     assert err.value.code == -2
 
 
+@pytest.mark.parametrize("method", ALL)
+@pytest.mark.parametrize("V,K", [(32000, 5), (32000, 20), (32000, 50), (4096, 5), (4096, 50), (70016, 20)])
+def test_rows_masked_down_to_a_few_tokens(method, V, K, request):
+    """bf16 rows with every logit at -inf except K tokens (what top-k filtering leaves), at even
+    and odd indices: most 32-bit words of such a row hold no finite upper half, so a softmax
+    shift estimated from whole words finds nothing to refer to in most waves.  Normalisers, leaf
+    draws and the draft records must still be those of the exact softmax (rows in registers at
+    V = 4096 and 32000, streamed at 70016)."""
+    k, depth, Bn = 2, 3, 6
+    N = W.tree_nodes(k, depth)
+    t, d = W.topk_masked_logits(Bn, N, V, K, seed=V + K, device=DEV)
+    wl = W.Workload("topk_V%d_K%d" % (V, K), Bn, N, V, k, depth, "bf16", "logits", 1.0, 1.0, t, d)
+    note(request, check_case(method, wl, seed=K))
+
+
+# ----------------------------------------------------------------- every dispatched kernel variant
+# (dtype, kind, V, row offset in elements): between them these reach every instantiation the
+# launchers can choose: rows in registers with 4, 8 or 16 chunks per lane, with and without masked
+# first / last chunks, fp32 and bf16, logits and probabilities, and the streamed forms.
+_VARIANTS = [
+    ("fp32", "logits", 12000, 0),    # fp32, 8 chunks per lane, no masking
+    ("fp32", "logits", 12001, 0),    # ... masked (ld = V is odd: rows start on every 4-byte phase)
+    ("fp32", "logits", 30000, 1),    # fp32, 16 chunks per lane, masked (base one element off)
+    ("fp32", "logits", 40000, 0),    # fp32, streamed
+    ("bf16", "logits", 20001, 0),    # bf16, 8 chunks per lane, masked
+    ("bf16", "logits", 50304, 0),    # bf16, 16 chunks per lane, no masking
+    ("bf16", "logits", 50257, 0),    # ... masked
+    ("bf16", "logits", 65520, 0),    # the longest row that stays in registers
+    ("bf16", "probs", 1000, 0),      # bf16 probabilities: registers
+    ("bf16", "probs", 4099, 3),      # ... masked
+    ("bf16", "probs", 40000, 0),     # ... 16 chunks per lane / streamed
+    ("bf16", "probs", 70016, 0),     # ... streamed
+    ("fp32", "probs", 20000, 0),     # fp32 probabilities, 16 chunks per lane
+    ("fp32", "probs", 40000, 0),     # ... streamed
+]
+
+
+@pytest.mark.parametrize("method", ALL)
+@pytest.mark.parametrize("dtype,kind,V,off", _VARIANTS, ids=["%s_%s_V%d_off%d" % v for v in _VARIANTS])
+def test_dispatched_variants(method, dtype, kind, V, off, request):
+    k, depth, Bn = (2, 3, 3) if method == "spechub" else (3, 2, 4)
+    N = W.tree_nodes(k, depth)
+    td = torch.float32 if dtype == "fp32" else torch.bfloat16
+    if kind == "logits":
+        t, d = W.llm_like_logits(Bn, N, V, logit_std=3.0, draft_noise_std=1.5, dtype=td, seed=V, device=DEV)
+        temps = (0.9, 1.2)
+    else:
+        # probabilities rounded to the storage type: used as given, not renormalised
+        lt, ld = W.llm_like_logits(Bn, N, V, logit_std=3.0, draft_noise_std=1.5, dtype=torch.float32, seed=V, device=DEV)
+        t, d = torch.softmax(lt.double(), -1).to(td), torch.softmax(ld.double(), -1).to(td)
+        temps = (1.0, 1.0)
+    if off:
+        big_t = torch.zeros((Bn * N * V + off,), dtype=td, device=DEV)
+        big_d = torch.zeros((Bn * N * V + off,), dtype=td, device=DEV)
+        tv, dv = big_t[off:].view(Bn, N, V), big_d[off:].view(Bn, N, V)
+        tv.copy_(t)
+        dv.copy_(d)
+        t, d = tv, dv
+    wl = W.Workload("variant_%s_%s_V%d" % (dtype, kind, V), Bn, N, V, k, depth, dtype, kind, temps[0], temps[1], t, d)
+    note(request, check_case(method, wl, seed=V % 1000, full_outputs=V <= 20001))
+
+
 # ----------------------------------------------------------------- general topology
 @pytest.mark.parametrize("method", ALL)
 def test_unbalanced_tree(method, request):
@@ -219,6 +281,38 @@ def test_unbalanced_tree(method, request):
     wl = W.Workload("unbalanced", Bn, N, V, k, depth, "bf16", "logits", 1.0, 1.0, t, d,
                     first_child=torch.tensor(fc, dtype=torch.int32, device=DEV))
     note(request, check_case(method, wl, seed=21))
+
+
+@pytest.mark.parametrize("method", ["rrs", "rrsw"])
+def test_unbalanced_ternary_tree(method, request):
+    """first_child given, three children per internal node: 0->(1,2,3) 1->(4,5,6) 3->(7,8,9)
+    6->(10,11,12); nodes 2, 4, 5 and the last level are leaves."""
+    fc = [1, 4, -1, 7, -1, -1, 10, -1, -1, -1, -1, -1, -1]
+    N, k, depth, V, Bn = len(fc), 3, 4, 3000, 10
+    t, d = W.llm_like_logits(Bn, N, V, logit_std=3.0, draft_noise_std=1.0, dtype=torch.bfloat16, seed=22, device=DEV)
+    wl = W.Workload("unbalanced3", Bn, N, V, k, depth, "bf16", "logits", 1.0, 1.0, t, d,
+                    first_child=torch.tensor(fc, dtype=torch.int32, device=DEV))
+    note(request, check_case(method, wl, seed=22))
+
+
+def test_first_child_entries_that_cannot_be_children_count_as_leaves():
+    """An entry that does not point past its own node, or leaves no room for k children, makes
+    the node a leaf in the verify kernels and in the walk alike (so the walk always ends)."""
+    good = [1, 3, -1, -1, -1]
+    for bad in ([1, 3, -1, 0, -1], [1, 3, -1, 3, -1], [1, 3, -1, 4, -1], [1, 3, 1, -1, -1]):
+        N, k, depth, V, Bn = 5, 2, 4, 500, 4
+        t, d = W.llm_like_logits(Bn, N, V, logit_std=3.0, draft_noise_std=1.0, dtype=torch.float32, seed=23, device=DEV)
+        u_v = B.philox_uniform(23, 2, Bn * N, k + 1, device=DEV).view(Bn, N, k + 1)
+        u_d = B.philox_uniform(23, 1, Bn * N, k, device=DEV).view(Bn, N, k)
+        res = []
+        for fc in (good, bad):
+            pb = B.Problem(t, d, B.LOGITS, k, depth, first_child=torch.tensor(fc, dtype=torch.int32, device=DEV))
+            tok = B.spechub_draft(B.Problem(t, d, B.LOGITS, k, depth,
+                                            first_child=torch.tensor(good, dtype=torch.int32, device=DEV)), u_d)["tokens"]
+            res.append(B.spechub_verify(pb, tok, u_v, flags=True, walk=True))
+            torch.cuda.synchronize()
+        for key in ("outcome", "token", "accept_depth", "emitted"):
+            assert torch.equal(res[0][key], res[1][key]), (bad, key)
 
 
 # ----------------------------------------------------------------- degenerate and invalid inputs
