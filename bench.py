@@ -3,7 +3,8 @@
 
 A step = one pass of the whole path over one batch of synthetic token trees:
 spechub_draft (pair sampling for every internal node), spechub_verify (every
-node) and the tree walk.  Inputs are resident in HBM; the step rotates over
+node) and the tree walk, which the verify kernel runs itself (two launches per
+step; --separate-walk makes the walk a third launch).  Inputs are resident in HBM; the step rotates over
 several distinct copies of the batch so that the working set exceeds the
 256 MiB Infinity Cache and "HBM GB/s" is not cache bandwidth.
 
@@ -23,6 +24,15 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 METRIC = "verified tree nodes/sec and HBM GB/s (% peak) at V=32000, 31-node tree"
+KERNEL_REPS = 200       # launches in each differential event bracket, whatever --steps is
+
+
+def metric_name(wl):
+    """The headline metric's name; for another workload than the headline's, the same metric
+    with that workload's vocabulary and tree size."""
+    if wl.V == 32000 and wl.N == 31:
+        return METRIC
+    return "verified tree nodes/sec and HBM GB/s (%% peak) at V=%d, %d-node tree" % (wl.V, wl.N)
 
 
 def parse():
@@ -39,6 +49,9 @@ def parse():
     ap.add_argument("--no-stats", action="store_true",
                     help="spechub_verify recomputes the draft row's hub and normalisers instead of "
                          "taking them from spechub_draft")
+    ap.add_argument("--separate-walk", action="store_true",
+                    help="three launches per step (draft, verify, walk) instead of two (the verify kernel "
+                         "walks each tree itself when the tree's last node is done)")
     ap.add_argument("--graph", action="store_true",
                     help="replay one HIP graph per step instead of launching its three kernels one by one "
                          "(measured slower on this workload: 63.9 against 59.8 us per step)")
@@ -51,8 +64,9 @@ def parse():
 
 
 def read_traffic(kernel_key: str):
-    """HBM bytes per launch measured offline with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
-    kept as a small text summary under profiles/; None when no summary exists."""
+    """HBM bytes per launch measured OFFLINE with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE) in runs
+    of this same command, kept as a small text summary under profiles/ (a counter run cannot be
+    made from inside the timed process); None when no summary exists for this kernel and workload."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     if not os.path.exists(path):
         return None
@@ -116,15 +130,21 @@ def main():
     plans = [B.StepPlan(args.method, pbs[i], u_d[i], u_v[i], hand_stats=not args.no_stats) for i in range(copies)]
     stream = B._stream()
 
+    fused = not args.separate_walk
+
     def step(i, ev=None):
         pl = plans[i % copies]
         pl.draft(stream)
         if ev is not None:
             ev[0].record()
-        pl.verify(stream)
+        if fused:
+            pl.verify_and_walk(stream)
+        else:
+            pl.verify(stream)
         if ev is not None:
             ev[1].record()
-        pl.walk(stream)
+        if not fused:
+            pl.walk(stream)
         return pl.out["accept_depth"]
 
     if args.calibration_copy:
@@ -148,8 +168,11 @@ def main():
             with torch.cuda.graph(g, stream=side):
                 st = B._stream()
                 pl.draft(st)
-                pl.verify(st)
-                pl.walk(st)
+                if fused:
+                    pl.verify_and_walk(st)
+                else:
+                    pl.verify(st)
+                    pl.walk(st)
             graphs.append(g)
         torch.cuda.synchronize()
         # a replay must give what the eager step gives (checked on every copy, twice, with eager work between)
@@ -179,7 +202,7 @@ def main():
     dt = time.perf_counter() - t0
     # the verify kernel inside eager steps, bracketed by events on the launch stream
     events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-              for _ in range(min(args.steps, 200))]
+              for _ in range(KERNEL_REPS)]
     for i, ev in enumerate(events):
         step(i, ev)
     torch.cuda.synchronize()
@@ -192,26 +215,35 @@ def main():
     # bracket around two launches and a bracket around one, both measured after the timed
     # region on the rotating inputs: the markers cancel, one launch (with the gap to its
     # neighbour) remains.  rocprofv3's kernel trace, which has no markers, is the cross-check.
-    reps = min(args.steps, 200)
-    one = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-    two = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-    for i in range(reps):
-        a, b = plans[(2 * i) % copies], plans[(2 * i + 1) % copies]
-        a.draft(stream)
-        b.draft(stream)
-        one[i][0].record()
-        a.verify(stream)
-        one[i][1].record()
-        two[i][0].record()
-        b.verify(stream)
-        a.verify(stream)
-        two[i][1].record()
-    torch.cuda.synchronize()
-    one_ms = sum(e0.elapsed_time(e1) for e0, e1 in one) / reps
-    two_ms = sum(e0.elapsed_time(e1) for e0, e1 in two) / reps
-    kernel_ms = two_ms - one_ms
+    reps = KERNEL_REPS
+
+    def differential(prepare, launch):
+        """Average duration of launch(plan): (bracket around two launches) - (bracket around one)."""
+        one = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        two = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for i in range(reps):
+            a, b = plans[(2 * i) % copies], plans[(2 * i + 1) % copies]
+            prepare(a)
+            prepare(b)
+            one[i][0].record()
+            launch(a)
+            one[i][1].record()
+            two[i][0].record()
+            launch(b)
+            launch(a)
+            two[i][1].record()
+        torch.cuda.synchronize()
+        one_ms = sum(e0.elapsed_time(e1) for e0, e1 in one) / reps
+        two_ms = sum(e0.elapsed_time(e1) for e0, e1 in two) / reps
+        return two_ms - one_ms, one_ms
+
+    verify_launch = (lambda pl: pl.verify_and_walk(stream)) if fused else (lambda pl: pl.verify(stream))
+    kernel_ms, one_ms = differential(lambda pl: pl.draft(stream), verify_launch)
     event_overhead_ms = one_ms - kernel_ms
     achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
+    draft_ms, _ = differential(lambda pl: None, lambda pl: pl.draft(stream))
+    es = 2 if wl0.dtype == "bf16" else 4
+    draft_bytes = Bn * wl0.n_internal * wl0.V * es
     # Reference line: a plain device copy of the same target rows (the library's copy kernel,
     # nothing of the method), timed the same way on the rotating copies: what a kernel that only
     # moves bytes reaches on a buffer of this size (it reads and writes, so twice the bytes).
@@ -238,33 +270,55 @@ def main():
     tps = float(ad.float().mean().item()) + 1.0
     kernel_key = "%s_verify:%s" % (args.method, wl0.name)
     traffic = read_traffic(kernel_key)
+    draft_traffic = read_traffic("%s_draft:%s" % (args.method, wl0.name))
 
     out = {
-        "metric": METRIC, "value": nodes_per_s, "unit": "nodes/s", "n_gpus": 1,
+        "metric": metric_name(wl0), "value": nodes_per_s, "unit": "nodes/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl0.name, "method": args.method, "B": Bn, "nodes_per_tree": N, "V": wl0.V,
                    "k": k, "storage": wl0.dtype, "temperature": wl0.temp_target,
-                   "step": "draft+verify+walk", "launch": "hip graph replay" if graphs else "three launches",
+                   "step": "draft+verify+walk",
+                   "launch": "hip graph replay" if graphs else
+                             ("two launches (walk inside the verify kernel)" if fused else "three launches"),
                    "input_copies_rotated": copies,
                    "early_exit": True,
                    "draft_stats_handed_to_verify": not args.no_stats,
                    "tokens_per_step_last_batch": tps},
+        # achieved = ALGORITHMIC bytes (every needed row once: the target row of every node, the draft
+        # row of every internal node) / kernel time.  With the draft call's records and early exit
+        # the kernel skips the draft rows of nodes decided by their first test, so it moves fewer
+        # bytes than that: `traffic` (rocprofv3 counters, offline) and `frac_of_bytes_moved` say
+        # what the memory system really did.
         "roofline": {"bound": "hbm", "kernel": "%s_verify" % args.method, "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "achieved_is": "algorithmic bytes (includes rows an early exit skips) / kernel time",
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": kernel_ms,
+                     "kernel_reps": reps,
                      "event_bracket_ms": bracket_ms, "event_overhead_ms": event_overhead_ms,
                      "traffic": traffic,
+                     "traffic_source": None if traffic is None else
+                                       "offline: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, profiles/hbm_traffic.txt",
                      "hbm_measured_gbs": None if traffic is None else traffic / (kernel_ms * 1e-3) / 1e9,
+                     "frac_of_bytes_moved": None if traffic is None else traffic / (kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "plain_copy_reference": {"gbs": plain_copy_gbs, "bytes": copy_bytes,
                                               "what": "device copy of the target rows of one input copy, "
                                                       "bytes read + written"}},
+        "other_kernels": {"%s_draft" % args.method: {
+            "kernel_ms": draft_ms, "algorithmic_bytes_per_launch": draft_bytes,
+            "achieved": draft_bytes / (draft_ms * 1e-3) / 1e9 if draft_ms > 0 else None,
+            "frac": draft_bytes / (draft_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if draft_ms > 0 else None,
+            "traffic": draft_traffic}},
+        "whole_step": {"algorithmic_bytes": alg_bytes, "gbs": alg_bytes / (ms_per_step * 1e-3) / 1e9,
+                       "frac": alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "what": "the verify call's algorithmic bytes over the whole step's time "
+                               "(the draft call re-reads the draft rows: not counted twice)"},
     }
     if not args.no_path_only:
         # the same step with verification restricted to the nodes the walk visits (the walk is
         # inside that kernel); reported beside the headline, never as it
-        psteps = min(args.steps, 200)
+        psteps = KERNEL_REPS
         for i in range(min(args.warmup, 10)):
             plans[i % copies].draft(stream)
             plans[i % copies].verify_path(stream)

@@ -77,8 +77,8 @@ extern "C" {
 #define MDSD_E_K (-3)         /* k outside 1..MDSD_MAX_K, or SpecHub with k != 2 (Sec. 4) */
 #define MDSD_E_TEMP (-4)      /* kind == logits and a temperature is not > 0    */
 #define MDSD_E_DTYPE (-5)     /* unknown dtype or kind                          */
-#define MDSD_E_ALIGN (-6)     /* pointer not element-aligned, or target/draft rows differ modulo 16 bytes */
-#define MDSD_E_WORKSPACE (-7) /* workspace smaller than mdsd_workspace_bytes()  */
+#define MDSD_E_ALIGN (-6)     /* pointer not element-aligned (workspace: 4 bytes), or target/draft rows differ modulo 16 bytes */
+#define MDSD_E_WORKSPACE (-7) /* a workspace was given and is smaller than mdsd_workspace_bytes() */
 #define MDSD_E_LAUNCH (-8)    /* the HIP runtime refused a launch               */
 #define MDSD_E_UNSUPPORTED (-9) /* an output this entry point cannot give was asked for */
 
@@ -154,7 +154,22 @@ typedef struct mdsd_result {
                               step = accept_depth + 1 (Sec. 5.3 batch efficiency)              */
 } mdsd_result;
 
-/* Bytes of device workspace the calls below need for this problem (may be 0). */
+/*
+ * Workspace.  No call needs one: ws may always be NULL.  spechub_verify, rrs_verify and
+ * rrsw_verify put a non-NULL workspace to use when they are also asked for the walk
+ * (out->accept_depth and out->emitted): it holds one int32 arrival counter per tree, with which
+ * the verify kernel walks each tree itself as soon as the tree's last node is done, instead of
+ * running the walk as a second launch behind it (same results; one launch less per step).
+ *   - mdsd_workspace_bytes(pb) = 4 * pb->B bytes; ws must be 4-byte aligned device memory;
+ *     a smaller ws_bytes is MDSD_E_WORKSPACE.
+ *   - The counters must be ZERO when the call starts.  Every call leaves them zero again, so a
+ *     workspace zero-filled once after its allocation can be handed to call after call.  (If a
+ *     call was cut short -- the process went on after a failed launch or a device error -- fill
+ *     it with zeros again; counters that do not start at zero give a wrong or missing walk,
+ *     never an access outside the arrays.)
+ *   - Calls that overlap in time (different streams) need workspaces of their own.
+ * The draft calls, the *_verify_path calls and mdsd_tree_walk ignore ws.
+ */
 size_t mdsd_workspace_bytes(const mdsd_problem* pb);
 
 /*

@@ -240,7 +240,15 @@ def alloc_result(pb: Problem, *, resid_mass=False, flags=True, resid_prob=False,
     return out
 
 
-def _verify(fn_name, pb: Problem, tokens: torch.Tensor, u: torch.Tensor, out, **want):
+def alloc_workspace(pb: Problem) -> torch.Tensor:
+    """A zero-filled workspace for the verify calls (one arrival counter per tree): handed to a
+    verify call together with walk=True, the kernel walks the trees itself.  Every call leaves
+    it zero-filled, so one workspace serves call after call on one stream."""
+    n = workspace_bytes(pb)
+    return torch.zeros(((n + 3) // 4,), dtype=torch.int32, device=pb.draft.device)
+
+
+def _verify(fn_name, pb: Problem, tokens: torch.Tensor, u: torch.Tensor, out, workspace=None, **want):
     cp = _c_problem(pb)
     if pb.target is None:
         raise ValueError("verify needs target rows")
@@ -255,24 +263,27 @@ def _verify(fn_name, pb: Problem, tokens: torch.Tensor, u: torch.Tensor, out, **
         if t is not None and not (t.is_cuda and t.is_contiguous()):
             raise ValueError("output %s must be a contiguous GPU tensor" % name)
         setattr(res, name, None if t is None else t.data_ptr())
-    rc = getattr(lib(), fn_name)(C.byref(cp), _ptr(tokens), _ptr(u), C.byref(res), None, 0, _stream())
+    if workspace is not None and not (workspace.is_cuda and workspace.is_contiguous()):
+        raise ValueError("workspace must be a contiguous GPU tensor")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = getattr(lib(), fn_name)(C.byref(cp), _ptr(tokens), _ptr(u), C.byref(res), _ptr(workspace), ws_bytes, _stream())
     if rc != 0:
         raise MdsdError(rc, fn_name)
     return out
 
 
-def spechub_verify(pb: Problem, tokens, u, out=None, **want):
+def spechub_verify(pb: Problem, tokens, u, out=None, workspace=None, **want):
     """Alg. 3 on every node plus the tree walk.  -> dict(outcome, token, [resid_mass],
     [flags], [resid_prob], [accept_depth, emitted])."""
-    return _verify("spechub_verify", pb, tokens, u, out, **want)
+    return _verify("spechub_verify", pb, tokens, u, out, workspace, **want)
 
 
-def rrs_verify(pb: Problem, tokens, u, out=None, **want):
-    return _verify("rrs_verify", pb, tokens, u, out, **want)
+def rrs_verify(pb: Problem, tokens, u, out=None, workspace=None, **want):
+    return _verify("rrs_verify", pb, tokens, u, out, workspace, **want)
 
 
-def rrsw_verify(pb: Problem, tokens, u, out=None, **want):
-    return _verify("rrsw_verify", pb, tokens, u, out, **want)
+def rrsw_verify(pb: Problem, tokens, u, out=None, workspace=None, **want):
+    return _verify("rrsw_verify", pb, tokens, u, out, workspace, **want)
 
 
 def spechub_verify_path(pb: Problem, tokens, u, out=None, **want):
@@ -342,6 +353,17 @@ class StepPlan:
             self._draft = lambda st: fn(pbp, ud, tk, df, None, 0, st)
         vfn = {"spechub": L.spechub_verify, "rrs": L.rrs_verify, "rrsw": L.rrsw_verify}[method]
         self._verify = lambda st: vfn(pbp, tk, uv, resp, None, 0, st)
+        # verify with the walk inside its kernel: the result structure carries the walk outputs
+        # and the call gets the (zero-filled, self-resetting) workspace
+        self.workspace = alloc_workspace(pb)
+        wsp, wsn = _ptr(self.workspace), self.workspace.numel() * 4
+        fres = _Result()
+        for name in ("outcome", "token", "flags", "accept_depth", "emitted"):
+            t = self.out.get(name)
+            setattr(fres, name, None if t is None else t.data_ptr())
+        self._fres = fres
+        fresp = C.byref(fres)
+        self._verify_walk = lambda st: vfn(pbp, tk, uv, fresp, wsp, wsn, st)
         # path-only: its result structure carries the walk outputs, the walk is in the kernel
         pres = _Result()
         for name in ("outcome", "token", "flags", "accept_depth", "emitted"):
@@ -364,6 +386,12 @@ class StepPlan:
         if rc != 0:
             raise MdsdError(rc, self.method + "_verify")
 
+    def verify_and_walk(self, stream=None):
+        """verify with the tree walk inside its kernel (one launch)."""
+        rc = self._verify_walk(_stream() if stream is None else stream)
+        if rc != 0:
+            raise MdsdError(rc, self.method + "_verify")
+
     def verify_path(self, stream=None):
         rc = self._verify_path(_stream() if stream is None else stream)
         if rc != 0:
@@ -377,8 +405,7 @@ class StepPlan:
     def run(self, stream=None):
         st = _stream() if stream is None else stream
         self.draft(st)
-        self.verify(st)
-        self.walk(st)
+        self.verify_and_walk(st)
         return self.out
 
 

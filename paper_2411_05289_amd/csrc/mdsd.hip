@@ -7,68 +7,14 @@
 namespace mdsd {
 
 // ---------------------------------------------------------------- tree walk
-// Sec. 2: follow the accepted children from the root; every visited node emits its token; stop at
-// the first node without an accepted child.  A first_child entry that does not point past its own
-// node or leaves no room for k children inside the tree counts as a leaf, the rule the verify
-// kernels apply to the same table: node numbers grow along the walk, which therefore ends.
-__device__ __forceinline__ int walk_first_child(const int32_t* first_child, int n, int k, int N)
+// The walk as a launch of its own: one wavefront per tree (see wave_walk in node_common.h).
+__global__ __launch_bounds__(256) void tree_walk_kernel(const int32_t* outcome, const int32_t* token, int B, int N,
+                                                        int k, int depth, const int32_t* first_child,
+                                                        int32_t* accept_depth, int32_t* emitted)
 {
-    if (first_child) {
-        const int c0 = first_child[n];
-        return (c0 <= n || c0 + k > N) ? -1 : c0;
-    }
-    const int64_t c = (int64_t)k * n + 1;
-    return (c + k <= N) ? (int)c : -1;
-}
-
-// Trees of at most 64 nodes: one wavefront per tree.  Lane n fetches node n's outcome, token and
-// first child, so the whole tree arrives in one trip to memory; the walk itself then runs on
-// registers (the node number is the same in every lane).
-__global__ __launch_bounds__(256) void tree_walk_wave_kernel(const int32_t* outcome, const int32_t* token, int B,
-                                                             int N, int k, int depth, const int32_t* first_child,
-                                                             int32_t* accept_depth, int32_t* emitted)
-{
-    const int lane = threadIdx.x & 63;
     const int b = blockIdx.x * (blockDim.x / 64) + (int)(threadIdx.x / 64);
     if (b >= B) return;
-    const bool in_tree = lane < N;
-    const int oc = in_tree ? outcome[(int64_t)b * N + lane] : -1;
-    const int tk = in_tree ? token[(int64_t)b * N + lane] : -1;
-    const int c0 = in_tree ? walk_first_child(first_child, lane, k, N) : -1;
-    int32_t* em = emitted + (int64_t)b * depth;
-    int n = 0, d = 0, mine = -1;  // lane d keeps the token emitted at depth d (d < 64)
-    for (;;) {
-        const int t = __shfl(tk, n, 64), o = __shfl(oc, n, 64), c = __shfl(c0, n, 64);
-        if (lane == d) mine = t;
-        if (c < 0 || o < 0 || o >= k || d + 1 >= depth || d + 1 >= 64) break;
-        n = c + o;  // < N: c + k <= N
-        ++d;
-    }
-    for (int i = lane; i < depth; i += 64) em[i] = i < 64 ? mine : -1;
-    if (lane == 0) accept_depth[b] = d;
-}
-
-// Larger trees: one thread per tree, node after node from memory.
-__global__ void tree_walk_kernel(const int32_t* outcome, const int32_t* token, int B, int N, int k,
-                                 int depth, const int32_t* first_child, int32_t* accept_depth,
-                                 int32_t* emitted)
-{
-    const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= B) return;
-    const int32_t* oc = outcome + (int64_t)b * N;
-    const int32_t* tk = token + (int64_t)b * N;
-    int32_t* em = emitted + (int64_t)b * depth;
-    for (int i = 0; i < depth; ++i) em[i] = -1;
-    int n = 0, d = 0;
-    for (;;) {
-        if (d < depth) em[d] = tk[n];
-        const int c0 = walk_first_child(first_child, n, k, N);
-        const int o = oc[n];
-        if (c0 < 0 || o < 0 || o >= k || d + 1 >= depth) break;
-        n = c0 + o;
-        ++d;
-    }
-    accept_depth[b] = d;
+    wave_walk<false>(outcome, token, b, N, k, depth, first_child, accept_depth, emitted);
 }
 
 // ---------------------------------------------------------------- Philox4x32-10
@@ -251,22 +197,20 @@ static void launch_draft(int method, const mdsd_problem* pb, const Params& P, hi
 static int walk(const mdsd_problem* pb, const int32_t* outcome, const int32_t* token,
                 int32_t* accept_depth, int32_t* emitted, hipStream_t st)
 {
-    if (pb->N <= 64) {
-        const int trees_per_block = 4;
-        hipLaunchKernelGGL(tree_walk_wave_kernel, dim3((pb->B + trees_per_block - 1) / trees_per_block),
-                           dim3(64 * trees_per_block), 0, st, outcome, token, pb->B, pb->N, pb->k, pb->depth,
-                           pb->first_child, accept_depth, emitted);
-    } else {
-        const int threads = 64;
-        hipLaunchKernelGGL(tree_walk_kernel, dim3((pb->B + threads - 1) / threads), dim3(threads), 0, st,
-                           outcome, token, pb->B, pb->N, pb->k, pb->depth, pb->first_child, accept_depth,
-                           emitted);
-    }
+    const int trees_per_block = 4;
+    hipLaunchKernelGGL(tree_walk_kernel, dim3((pb->B + trees_per_block - 1) / trees_per_block),
+                       dim3(64 * trees_per_block), 0, st, outcome, token, pb->B, pb->N, pb->k, pb->depth,
+                       pb->first_child, accept_depth, emitted);
     return hipGetLastError() == hipSuccess ? MDSD_OK : MDSD_E_LAUNCH;
 }
 
+// bytes of workspace the full verify calls take when they walk the trees themselves
+static size_t walk_workspace_bytes(int B) { return B > 0 ? (size_t)B * sizeof(int32_t) : 0; }
+
+// tree_count: per-tree arrival counters (zero on entry) when the kernel is to walk the trees
+// itself, nullptr when the walk is a launch of its own
 static int verify_entry(int method, const mdsd_problem* pb, const int32_t* tokens, const float* u,
-                        const mdsd_result* out, bool path, void* stream)
+                        const mdsd_result* out, bool path, int32_t* tree_count, void* stream)
 {
     Params P = {};
     const int rc = validate(pb, method, true, &P);
@@ -276,8 +220,10 @@ static int verify_entry(int method, const mdsd_problem* pb, const int32_t* token
     if ((out->accept_depth == nullptr) != (out->emitted == nullptr)) return MDSD_E_NULL;
     if (path && !out->accept_depth) return MDSD_E_NULL;
     if (path && out->resid_prob) return MDSD_E_UNSUPPORTED;
+    const bool walk_inside = !path && out->accept_depth && tree_count;
     P.accept_depth = out->accept_depth;
     P.emitted = out->emitted;
+    P.tree_count = walk_inside ? tree_count : nullptr;
     P.tokens = tokens;
     P.u = u;
     P.outcome = out->outcome;
@@ -290,9 +236,18 @@ static int verify_entry(int method, const mdsd_problem* pb, const int32_t* token
     (void)hipGetLastError();
     launch_verify(method, pb, P, path, st);
     if (hipGetLastError() != hipSuccess) return MDSD_E_LAUNCH;
-    if (path) return MDSD_OK;  // the walk is part of the kernel
+    if (path || walk_inside) return MDSD_OK;  // the walk is part of the kernel
     if (out->accept_depth) return walk(pb, out->outcome, out->token, out->accept_depth, out->emitted, st);
     return MDSD_OK;
+}
+
+// the full verify calls: a workspace, when given, holds the trees' arrival counters
+static int verify_with_workspace(int method, const mdsd_problem* pb, const int32_t* tokens, const float* u,
+                                 const mdsd_result* out, void* ws, size_t ws_bytes, void* stream)
+{
+    if (ws && pb && ws_bytes < walk_workspace_bytes(pb->B)) return MDSD_E_WORKSPACE;
+    if (ws && ((uintptr_t)ws & 3)) return MDSD_E_ALIGN;
+    return verify_entry(method, pb, tokens, u, out, false, (int32_t*)ws, stream);
 }
 
 static int draft_entry(int method, const mdsd_problem* pb, const float* u, int32_t* tokens,
@@ -321,8 +276,9 @@ extern "C" {
 
 size_t mdsd_workspace_bytes(const mdsd_problem* pb)
 {
-    (void)pb;
-    return 0;  // every intermediate lives in registers and LDS
+    // every intermediate of a node lives in registers and LDS; the workspace holds one arrival
+    // counter per tree for the verify calls that walk the trees inside their kernel
+    return pb ? mdsd::walk_workspace_bytes(pb->B) : 0;
 }
 
 int spechub_draft(const mdsd_problem* pb, const float* u, int32_t* tokens, int32_t* hub, int32_t* flags,
@@ -352,25 +308,19 @@ int rrsw_draft(const mdsd_problem* pb, const float* u, int32_t* tokens, int32_t*
 int spechub_verify(const mdsd_problem* pb, const int32_t* tokens, const float* u, const mdsd_result* out,
                    void* ws, size_t ws_bytes, void* stream)
 {
-    (void)ws;
-    (void)ws_bytes;
-    return mdsd::verify_entry(mdsd::kSpecHub, pb, tokens, u, out, false, stream);
+    return mdsd::verify_with_workspace(mdsd::kSpecHub, pb, tokens, u, out, ws, ws_bytes, stream);
 }
 
 int rrs_verify(const mdsd_problem* pb, const int32_t* tokens, const float* u, const mdsd_result* out,
                void* ws, size_t ws_bytes, void* stream)
 {
-    (void)ws;
-    (void)ws_bytes;
-    return mdsd::verify_entry(mdsd::kRRS, pb, tokens, u, out, false, stream);
+    return mdsd::verify_with_workspace(mdsd::kRRS, pb, tokens, u, out, ws, ws_bytes, stream);
 }
 
 int rrsw_verify(const mdsd_problem* pb, const int32_t* tokens, const float* u, const mdsd_result* out,
                 void* ws, size_t ws_bytes, void* stream)
 {
-    (void)ws;
-    (void)ws_bytes;
-    return mdsd::verify_entry(mdsd::kRRSw, pb, tokens, u, out, false, stream);
+    return mdsd::verify_with_workspace(mdsd::kRRSw, pb, tokens, u, out, ws, ws_bytes, stream);
 }
 
 int spechub_verify_path(const mdsd_problem* pb, const int32_t* tokens, const float* u, const mdsd_result* out,
@@ -378,7 +328,7 @@ int spechub_verify_path(const mdsd_problem* pb, const int32_t* tokens, const flo
 {
     (void)ws;
     (void)ws_bytes;
-    return mdsd::verify_entry(mdsd::kSpecHub, pb, tokens, u, out, true, stream);
+    return mdsd::verify_entry(mdsd::kSpecHub, pb, tokens, u, out, true, nullptr, stream);
 }
 
 int rrs_verify_path(const mdsd_problem* pb, const int32_t* tokens, const float* u, const mdsd_result* out,
@@ -386,7 +336,7 @@ int rrs_verify_path(const mdsd_problem* pb, const int32_t* tokens, const float* 
 {
     (void)ws;
     (void)ws_bytes;
-    return mdsd::verify_entry(mdsd::kRRS, pb, tokens, u, out, true, stream);
+    return mdsd::verify_entry(mdsd::kRRS, pb, tokens, u, out, true, nullptr, stream);
 }
 
 int rrsw_verify_path(const mdsd_problem* pb, const int32_t* tokens, const float* u, const mdsd_result* out,
@@ -394,7 +344,7 @@ int rrsw_verify_path(const mdsd_problem* pb, const int32_t* tokens, const float*
 {
     (void)ws;
     (void)ws_bytes;
-    return mdsd::verify_entry(mdsd::kRRSw, pb, tokens, u, out, true, stream);
+    return mdsd::verify_entry(mdsd::kRRSw, pb, tokens, u, out, true, nullptr, stream);
 }
 
 int mdsd_tree_walk(const mdsd_problem* pb, const int32_t* outcome, const int32_t* token,
@@ -436,13 +386,13 @@ const char* mdsd_strerror(int code)
     case MDSD_E_TEMP: return "temperature must be > 0";
     case MDSD_E_DTYPE: return "unknown dtype or kind";
     case MDSD_E_ALIGN: return "pointer not element-aligned, or target/draft rows differ modulo 16 bytes";
-    case MDSD_E_WORKSPACE: return "workspace too small";
+    case MDSD_E_WORKSPACE: return "workspace smaller than mdsd_workspace_bytes()";
     case MDSD_E_LAUNCH: return "HIP launch failed";
     case MDSD_E_UNSUPPORTED: return "output not available from this entry point";
     default: return "unknown status";
     }
 }
 
-int mdsd_version(void) { return 102; }
+int mdsd_version(void) { return 103; }
 
 }  // extern "C"

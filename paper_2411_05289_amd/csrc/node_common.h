@@ -53,8 +53,11 @@ struct Params {
     float* resid_mass;
     int32_t* flags;
     float* resid_prob;
-    int32_t* accept_depth;  // path-only kernels
+    int32_t* accept_depth;  // path-only kernels, and the full kernels when they walk the trees themselves
     int32_t* emitted;
+    // full verify kernels with the walk inside: one arrival counter per tree (all zero when the
+    // kernel starts, all zero again when it ends); nullptr = the walk is a launch of its own
+    int32_t* tree_count;
     // draft kernels
     int32_t* tokens_out;
     int32_t* hub_out;
@@ -125,6 +128,113 @@ __device__ __forceinline__ NodeId node_of_block(const Params& P)
     id.c0 = id.n < P.n_internal ? P.k * id.n + 1 : -1;
     id.row = (int64_t)id.b * P.N + id.n;
     return id;
+}
+
+// ---------------------------------------------------------------- tree walk and node outputs
+// Sec. 2: follow the accepted children from the root; every visited node emits its token; stop at
+// the first node without an accepted child.  A first_child entry that does not point past its own
+// node or leaves no room for k children inside the tree counts as a leaf, here as in
+// node_of_item(): node numbers grow along the walk, which therefore ends.
+__device__ __forceinline__ int walk_first_child(const int32_t* first_child, int n, int k, int N)
+{
+    if (first_child) {
+        const int c0 = first_child[n];
+        return (c0 <= n || c0 + k > N) ? -1 : c0;
+    }
+    const int64_t c = (int64_t)k * n + 1;
+    return (c + k <= N) ? (int)c : -1;
+}
+
+// One entry of outcome[] / token[].  COHERENT: the value was written by another workgroup of the
+// same launch, possibly on another XCD, whose L2 this one does not share: written and read with
+// device-scope atomic accesses (which go to memory), it is seen without flushing either cache.
+template <bool COHERENT>
+__device__ __forceinline__ int load_node_word(const int32_t* p)
+{
+    if constexpr (COHERENT)
+        return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else
+        return *p;
+}
+
+// The walk of tree b by one wavefront (all 64 lanes active, the same b in every lane).  Trees of
+// at most 64 nodes: lane n fetches node n, so the whole tree arrives in one trip to memory and
+// the walk runs on registers.  Larger trees: node after node from memory.
+template <bool COHERENT>
+__device__ __forceinline__ void wave_walk(const int32_t* outcome, const int32_t* token, int b, int N, int k,
+                                          int depth, const int32_t* first_child, int32_t* accept_depth,
+                                          int32_t* emitted)
+{
+    const int lane = threadIdx.x & 63;
+    const int32_t* oc = outcome + (int64_t)b * N;
+    const int32_t* tk = token + (int64_t)b * N;
+    int32_t* em = emitted + (int64_t)b * depth;
+    if (N <= 64) {
+        const bool in_tree = lane < N;
+        const int o_l = in_tree ? load_node_word<COHERENT>(oc + lane) : -1;
+        const int t_l = in_tree ? load_node_word<COHERENT>(tk + lane) : -1;
+        const int c_l = in_tree ? walk_first_child(first_child, lane, k, N) : -1;
+        int n = 0, d = 0, mine = -1;  // lane d keeps the token emitted at depth d (d < N <= 64)
+        for (;;) {
+            const int t = __shfl(t_l, n, 64), o = __shfl(o_l, n, 64), c = __shfl(c_l, n, 64);
+            if (lane == d) mine = t;
+            if (c < 0 || o < 0 || o >= k || d + 1 >= depth || d + 1 >= 64) break;
+            n = c + o;  // < N: c + k <= N
+            ++d;
+        }
+        for (int i = lane; i < depth; i += 64) em[i] = i < 64 ? mine : -1;
+        if (lane == 0) accept_depth[b] = d;
+    } else {
+        if (lane == 0) {
+            for (int i = 0; i < depth; ++i) em[i] = -1;
+            int n = 0, d = 0;
+            for (;;) {
+                const int t = load_node_word<COHERENT>(tk + n), o = load_node_word<COHERENT>(oc + n);
+                if (d < depth) em[d] = t;
+                const int c = walk_first_child(first_child, n, k, N);
+                if (c < 0 || o < 0 || o >= k || d + 1 >= depth) break;
+                n = c + o;
+                ++d;
+            }
+            accept_depth[b] = d;
+        }
+    }
+}
+
+// The outputs of one node, written by the first thread of the workgroup (whose copy of them is
+// always complete).  With P.tree_count the kernel also walks the trees: the workgroup that
+// brings a tree's last node walks it.  Its nodes' outcomes and tokens then cross from workgroup to
+// workgroup inside one launch: they are stored with device-scope atomic stores (which go to
+// memory), the store is waited for, and only then is the tree's arrival counted, so whoever
+// counts N arrivals finds every node's words in memory; it reads them with device-scope atomic
+// loads.  No cache is flushed or invalidated.  The counter is set back to 0 for the next launch.
+__device__ __forceinline__ void write_node_outputs(const Params& P, const NodeId& id, int outcome, int token,
+                                                   float rmass, int flags)
+{
+    if (threadIdx.x >= kWave) return;
+    const bool first = threadIdx.x == 0;
+    if (first) {
+        if (P.resid_mass) P.resid_mass[id.row] = rmass;
+        if (P.flags) P.flags[id.row] = flags;
+    }
+    if (P.tree_count == nullptr) {
+        if (first) {
+            P.outcome[id.row] = outcome;
+            P.token[id.row] = token;
+        }
+        return;
+    }
+    int arrived = 0;
+    if (first) {
+        __hip_atomic_store(P.outcome + id.row, outcome, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(P.token + id.row, token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // both stores have reached memory
+        arrived = __hip_atomic_fetch_add(P.tree_count + id.b, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    arrived = __builtin_amdgcn_readfirstlane(arrived);
+    if (arrived != P.N - 1) return;
+    wave_walk<true>(P.outcome, P.token, id.b, P.N, P.k, P.depth, P.first_child, P.accept_depth, P.emitted);
+    if (first) __hip_atomic_store(P.tree_count + id.b, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ---------------------------------------------------------------- passes

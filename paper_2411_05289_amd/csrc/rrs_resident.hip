@@ -249,12 +249,7 @@ __device__ __forceinline__ NodeOut rrs_node_resident(const Params& P, const Node
         const RowView rq = make_row<DT>(P.draft, P.ld_d, id.row, P.V);
         rrs_resident<DT, NIT, MASKED, WO>(P, id, rp, rq, sp, need_full, rprob, sh, phase, o);
     }
-    if (threadIdx.x == 0) {
-        P.outcome[id.row] = o.outcome;
-        P.token[id.row] = o.token;
-        if (P.resid_mass) P.resid_mass[id.row] = o.rmass;
-        if (P.flags) P.flags[id.row] = o.flags;
-    }
+    write_node_outputs(P, id, o.outcome, o.token, o.rmass, o.flags);
     return o;
 }
 

@@ -400,12 +400,7 @@ __device__ __forceinline__ NodeOut spechub_node_resident(const Params& P, const 
         leaf_resident<DT, NIT, MASKED, EVERY_WAVE>(P, rp, sp, in.u2, rprob, sh, phase, o);
     else
         spechub_resident<DT, NIT, MASKED, STATS, EVERY_WAVE>(P, in, rp, rq, sp, sq, need_full, rprob, sh, phase, o);
-    if (threadIdx.x == 0) {
-        P.outcome[id.row] = o.outcome;
-        P.token[id.row] = o.token;
-        if (P.resid_mass) P.resid_mass[id.row] = o.rmass;
-        if (P.flags) P.flags[id.row] = o.flags;
-    }
+    write_node_outputs(P, id, o.outcome, o.token, o.rmass, o.flags);
     return o;
 }
 

@@ -499,12 +499,7 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
         }
     }
 
-    if (threadIdx.x == 0) {
-        P.outcome[id.row] = outcome;
-        P.token[id.row] = token;
-        if (P.resid_mass) P.resid_mass[id.row] = rmass;
-        if (P.flags) P.flags[id.row] = flags;
-    }
+    write_node_outputs(P, id, outcome, token, rmass, flags);
     return NodeOut{outcome, token, flags, rmass};
 }
 

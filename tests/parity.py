@@ -126,6 +126,16 @@ def check_case(method: str, wl: Workload, seed: int = 0, seqs=None, full_outputs
             bad = (diff > tol) & ok_nodes[:, :, None]
             assert not bad.any(), "resid_prob off at %s (diff %g)" % (np.argwhere(bad)[:5], diff[bad].max())
             out["resid_prob_max_abs"] = float(diff[ok_nodes].max(initial=0.0))
+    # ---- the walk inside the verify kernel (a workspace of arrival counters handed in): the very
+    # same results as with the walk as a launch of its own, call after call on one workspace
+    ws = B.alloc_workspace(pb)
+    for _ in range(2):
+        g_ws = VERIFY[method](pb, tokens, u_v, workspace=ws, resid_mass=False, flags=True, walk=True)
+        for key in ("outcome", "token", "flags", "accept_depth", "emitted"):
+            assert torch.equal(g_ws[key], g_fast[key]), "walk inside the kernel: %s differs" % key
+        assert not ws.any(), "the arrival counters were not left at zero"
+    _compare_walk(wl, g_ws, o_v, idx, near)
+
     # ---- path-only verification: the walk's outputs, and the visited nodes, against the oracle
     g_path = VERIFY_PATH[method](pb, tokens, u_v, resid_mass=False, flags=True, walk=True)
     out["path_nodes_visited"] = _compare_path(wl, g_path, o_v, idx, near, "path")
@@ -142,6 +152,10 @@ def check_case(method: str, wl: Workload, seed: int = 0, seqs=None, full_outputs
         out["mismatch_in_band_stats"] = _compare_nodes(g_s, o_v, idx, near, "early-exit+stats", ctx)
         _compare_walk(wl, g_s, o_v, idx, near)
         assert out["mismatch_in_band_stats"] <= mismatch_allowance(near), out
+        g_ws = VERIFY[method](pb_s, tokens, u_v, workspace=ws, resid_mass=False, flags=True, walk=True)
+        for key in ("outcome", "token", "flags", "accept_depth", "emitted"):
+            assert torch.equal(g_ws[key], g_s[key]), "walk inside the kernel (stats): %s differs" % key
+        assert not ws.any()
         g_path_s = VERIFY_PATH[method](pb_s, tokens, u_v, resid_mass=False, flags=True, walk=True)
         _compare_path(wl, g_path_s, o_v, idx, near, "path+stats")
         if full_outputs:

@@ -115,9 +115,17 @@ def test_path_calls_need_the_walk_outputs_and_refuse_resid_prob(name):
     assert fn(C.byref(bad), C.c_void_p(0x5000), C.c_void_p(0x6000), C.byref(res), None, 0, None) == -2
 
 
-def test_workspace_is_zero():
+def test_workspace_is_one_counter_per_tree_and_checked():
     p = _problem()
-    assert B.lib().mdsd_workspace_bytes(C.byref(p)) == 0
+    assert B.lib().mdsd_workspace_bytes(C.byref(p)) == 4 * p.B
+    assert B.lib().mdsd_workspace_bytes(None) == 0
+    # a workspace that is too small, or not 4-byte aligned, is refused before anything is launched
+    res = B._Result()
+    res.outcome, res.token = 0x7000, 0x8000
+    res.accept_depth, res.emitted = 0x9000, 0xA000
+    fn = B.lib().spechub_verify
+    assert fn(C.byref(p), C.c_void_p(0x5000), C.c_void_p(0x6000), C.byref(res), C.c_void_p(0xB000), 4 * p.B - 1, None) == -7
+    assert fn(C.byref(p), C.c_void_p(0x5000), C.c_void_p(0x6000), C.byref(res), C.c_void_p(0xB002), 4 * p.B, None) == -6
 
 
 def test_binding_refuses_cpu_tensors():

@@ -315,6 +315,32 @@ def test_first_child_entries_that_cannot_be_children_count_as_leaves():
             assert torch.equal(res[0][key], res[1][key]), (bad, key)
 
 
+@pytest.mark.parametrize("method", ALL)
+def test_trees_of_more_than_64_nodes(method, request):
+    """127-node trees: the walk (as a launch of its own and inside the verify kernel) goes node
+    by node from memory instead of holding the tree in one wavefront's lanes."""
+    wl = W.config(3, device=DEV, B=5, V=600, depth=7, seed=61)
+    assert wl.N == 127
+    note(request, check_case(method, wl, seed=61, full_outputs=False))
+
+
+def test_workspace_is_checked():
+    wl = W.config(3, device=DEV, B=4, V=600, depth=3, seed=62)
+    pb = B.Problem.from_workload(wl)
+    assert B.workspace_bytes(pb) == 4 * wl.B
+    u_d, u_v = uniforms(wl, 62)
+    tokens = B.spechub_draft(pb, u_d)["tokens"]
+    small = torch.zeros((wl.B - 1,), dtype=torch.int32, device=DEV)
+    with pytest.raises(B.MdsdError) as err:
+        B.spechub_verify(pb, tokens, u_v, workspace=small)
+    assert err.value.code == -7
+    # without the walk outputs the workspace is left alone
+    ws = B.alloc_workspace(pb)
+    a = B.spechub_verify(pb, tokens, u_v, workspace=ws, walk=False)
+    b = B.spechub_verify(pb, tokens, u_v, walk=False)
+    assert torch.equal(a["outcome"], b["outcome"]) and not ws.any()
+
+
 # ----------------------------------------------------------------- degenerate and invalid inputs
 def _tiny_probs(p_rows, q_rows, k=2, depth=2):
     p = torch.tensor(p_rows, dtype=torch.float32, device=DEV).view(1, -1, len(p_rows[0]))
