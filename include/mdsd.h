@@ -205,6 +205,25 @@ int spechub_verify(const mdsd_problem* pb, const int32_t* tokens, const float* u
                    const mdsd_result* out, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * spechub_verify_static -- spechub_verify with the tree walk inside its kernel, for callers that
+ * cannot allocate or carry a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  The arrival counters live in a device array of the library's
+ * own (MDSD_STATIC_MAX_TREES int32, 256 KiB per GPU, held until the process ends); the call
+ * allocates nothing, frees nothing and queues one kernel on `stream`.
+ *   - Same arguments and results as spechub_verify with a workspace; out->accept_depth and
+ *     out->emitted are required (MDSD_E_NULL without them).
+ *   - pb->B > MDSD_STATIC_MAX_TREES is refused with MDSD_E_WORKSPACE.
+ *   - All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU
+ *     (different streams) race on it and may give wrong or missing walks; calls on one stream,
+ *     one after another, are fine.  Every call leaves the counters zero for the next.
+ *   - The first call on a device looks up the array's address on that device (no allocation);
+ *     the device must be current, as for every call.
+ */
+#define MDSD_STATIC_MAX_TREES 65536
+int spechub_verify_static(const mdsd_problem* pb, const int32_t* tokens, const float* u,
+                          const mdsd_result* out, void* stream);
+
+/*
  * rrs_draft / rrsw_draft -- Alg. 1, first step: k tokens per internal node from
  * q, independently (RRS) or without replacement (RRSw; Sec. 3.3 gives both Q).
  *   u device [B,N,k]; tokens device [B,N] out, child-indexed; flags or NULL.

@@ -22,7 +22,7 @@ PROBS, LOGITS = 0, 1
 NONE, BAD_PAIR, BAD_TOKEN, UNVISITED = -1, -2, -3, -4
 FLAG_DEGENERATE_HUB, FLAG_ZERO_RESIDUAL, FLAG_Q_EXHAUSTED, FLAG_BAD_PAIR, FLAG_BAD_TOKEN = 1, 2, 4, 8, 16
 
-EXPORTS = ("mdsd_workspace_bytes", "spechub_draft", "spechub_verify", "rrs_draft", "rrsw_draft",
+EXPORTS = ("mdsd_workspace_bytes", "spechub_draft", "spechub_verify", "spechub_verify_static", "rrs_draft", "rrsw_draft",
            "rrs_verify", "rrsw_verify", "spechub_verify_path", "rrs_verify_path", "rrsw_verify_path",
            "mdsd_tree_walk", "mdsd_philox_uniform", "mdsd_strerror", "mdsd_version")
 
@@ -82,6 +82,8 @@ def lib():
             f.restype = C.c_int
         for f in (L.spechub_draft, L.rrs_draft, L.rrsw_draft):
             f.restype = C.c_int
+        L.spechub_verify_static.argtypes = [C.c_void_p] * 5
+        L.spechub_verify_static.restype = C.c_int
         L.mdsd_tree_walk.argtypes = [C.c_void_p] * 6
         L.mdsd_tree_walk.restype = C.c_int
         L.mdsd_philox_uniform.argtypes = [C.c_uint64, C.c_uint32, C.c_int64, C.c_int32, C.c_void_p,
@@ -276,6 +278,25 @@ def spechub_verify(pb: Problem, tokens, u, out=None, workspace=None, **want):
     """Alg. 3 on every node plus the tree walk.  -> dict(outcome, token, [resid_mass],
     [flags], [resid_prob], [accept_depth, emitted])."""
     return _verify("spechub_verify", pb, tokens, u, out, workspace, **want)
+
+
+def spechub_verify_static(pb: Problem, tokens, u, out):
+    """spechub_verify with the walk inside its kernel on the library's own arrival counters: the
+    call allocates nothing (`out`, from alloc_result(..., walk=True), is the caller's)."""
+    cp = _c_problem(pb)
+    B, N, _ = pb.draft.shape
+    _check_dev(tokens, "tokens", torch.int32, (B, N))
+    _check_dev(u, "u", torch.float32, (B, N, pb.k + 1))
+    res = _Result()
+    for name in ("outcome", "token", "resid_mass", "flags", "resid_prob", "accept_depth", "emitted"):
+        t = out.get(name)
+        if t is not None and not (t.is_cuda and t.is_contiguous()):
+            raise ValueError("output %s must be a contiguous GPU tensor" % name)
+        setattr(res, name, None if t is None else t.data_ptr())
+    rc = lib().spechub_verify_static(C.byref(cp), _ptr(tokens), _ptr(u), C.byref(res), _stream())
+    if rc != 0:
+        raise MdsdError(rc, "spechub_verify_static")
+    return out
 
 
 def rrs_verify(pb: Problem, tokens, u, out=None, workspace=None, **want):

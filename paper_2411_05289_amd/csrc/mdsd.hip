@@ -4,6 +4,8 @@
 // kernels, and the C entry points.
 #include "launch.h"
 
+#include <atomic>
+
 namespace mdsd {
 
 // ---------------------------------------------------------------- tree walk
@@ -250,6 +252,34 @@ static int verify_with_workspace(int method, const mdsd_problem* pb, const int32
     return verify_entry(method, pb, tokens, u, out, false, (int32_t*)ws, stream);
 }
 
+// ---------------------------------------------------------------- arrival counters owned by the library
+// For callers that cannot allocate a workspace (code under HIP graph capture, serving loops that
+// must not call hipMalloc): the arrival counters of up to MDSD_STATIC_MAX_TREES trees in a
+// file-scope device array, zero when the code object is loaded and left zero by every call.  Each
+// GPU holds its own copy at its own address; the array's name is a host-side stand-in, so the
+// address on the current device is asked for once per device and used from then on.
+static __device__ __align__(256) int32_t scratch[MDSD_STATIC_MAX_TREES];
+
+static constexpr int kMaxDevices = 64;
+static std::atomic<int32_t*> scratch_on_device[kMaxDevices];
+
+static int static_tree_counters(int32_t** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MDSD_E_LAUNCH;
+    int32_t* ptr = scratch_on_device[dev].load(std::memory_order_acquire);
+    if (ptr == nullptr) {
+        // two threads asking at once get the same answer
+        if (hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+            (void)hipGetLastError();
+            return MDSD_E_LAUNCH;
+        }
+        scratch_on_device[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return MDSD_OK;
+}
+
 static int draft_entry(int method, const mdsd_problem* pb, const float* u, int32_t* tokens,
                        int32_t* hub, int32_t* flags, void* stream)
 {
@@ -309,6 +339,18 @@ int spechub_verify(const mdsd_problem* pb, const int32_t* tokens, const float* u
                    void* ws, size_t ws_bytes, void* stream)
 {
     return mdsd::verify_with_workspace(mdsd::kSpecHub, pb, tokens, u, out, ws, ws_bytes, stream);
+}
+
+int spechub_verify_static(const mdsd_problem* pb, const int32_t* tokens, const float* u, const mdsd_result* out,
+                          void* stream)
+{
+    if (!pb) return MDSD_E_NULL;
+    if (pb->B > MDSD_STATIC_MAX_TREES) return MDSD_E_WORKSPACE;
+    if (!out || !out->accept_depth || !out->emitted) return MDSD_E_NULL;
+    int32_t* counters = nullptr;
+    const int rc = mdsd::static_tree_counters(&counters);
+    if (rc != MDSD_OK) return rc;
+    return mdsd::verify_entry(mdsd::kSpecHub, pb, tokens, u, out, false, counters, stream);
 }
 
 int rrs_verify(const mdsd_problem* pb, const int32_t* tokens, const float* u, const mdsd_result* out,
