@@ -76,6 +76,52 @@ def test_closed_forms_match_the_oracle_on_a_tiny_vocabulary():
         assert got == pytest.approx(spechub_acceptance(p, q), abs=1e-9)
 
 
+# ----------------------------------------------------------------- the OTM columns (CPU, linear program)
+def test_lp_on_the_worked_example_and_against_the_heuristics():
+    """p = [.1, .6, .3], q = [.5, .3, .2] (the LP figure of Sec. 3): drawn without replacement the
+    optimal plan loses nothing, where RRSw loses 0.06.  Drawn with replacement, the pair (a, a)
+    has mass .25 and can only emit a, whose target probability is .1: at least .15 is lost, and
+    the LP loses no more.  On random
+    pairs the optimum is never below what RRS / RRSw accept (they are feasible plans for the same
+    Q), and never above sum_y min(p(y), mass of the pairs that hold y)."""
+    from otm_lp import joint_draft, optimal_acceptance
+    p, q = np.array([0.1, 0.6, 0.3]), np.array([0.5, 0.3, 0.2])
+    assert optimal_acceptance(p, joint_draft(q, True)) == pytest.approx(1.0, abs=1e-9)
+    assert rrsw_acceptance(p, q) == pytest.approx(0.94, abs=1e-12)
+    assert optimal_acceptance(p, joint_draft(q, False)) == pytest.approx(0.85, abs=1e-9)
+    rng = np.random.default_rng(7)
+    for _ in range(6):
+        p, q = rng.dirichlet(np.full(12, 0.6)), rng.dirichlet(np.full(12, 0.6))
+        for wo, heuristic in ((False, rrs_acceptance), (True, rrsw_acceptance)):
+            Q = joint_draft(q, wo)
+            best = optimal_acceptance(p, Q)
+            holds = Q.sum(axis=0) + Q.sum(axis=1) - np.diag(Q)      # mass of the pairs that hold y
+            assert heuristic(p, q) <= best + 1e-9 <= np.minimum(p, holds).sum() + 2e-9
+
+
+def test_otm_columns_of_the_toy_table():
+    """Soft pin: the OTM / OTMw columns (optimal acceptance for q x q and for draws without
+    replacement) on pairs of the toy recipe against the printed means over 100 pairs, and the
+    ordering the appendix reports: the optimum without replacement is the best column at
+    T = 0.5, SpecHub beats the with-replacement optimum at T = 0.1."""
+    from otm_lp import joint_draft, optimal_acceptance
+    pairs = 40
+    for T, lam, rrs_ref, rrsw_ref, otm_ref, otmw_ref, hub_ref in table_rows():
+        wl = W.toy_pairs(T, lam, pairs, seed=int(1000 * T + 10 * lam))
+        p = _softmax(wl.target[:, 0].numpy(), T)
+        q = _softmax(wl.draft[:, 0].numpy(), T)
+        otm = np.array([optimal_acceptance(p[i], joint_draft(q[i], False)) for i in range(pairs)])
+        otmw = np.array([optimal_acceptance(p[i], joint_draft(q[i], True)) for i in range(pairs)])
+        hub = np.array([spechub_acceptance(p[i], q[i]) for i in range(pairs)])
+        for got, ref in ((otm, otm_ref), (otmw, otmw_ref)):
+            assert abs(got.mean() - ref) < 3 * got.std() * np.sqrt(1 / pairs + 1 / 100) + 0.01, (T, lam, got.mean(), ref)
+        assert (otmw >= otm - 1e-9).mean() > 0.9          # taking tokens out never hurts much
+        if T == 0.5:
+            assert otmw.mean() > hub.mean()
+        if T == 0.1:
+            assert hub.mean() > otm.mean()
+
+
 def table_rows():
     return [[float(t) for t in line.split()] for line in open(os.path.join(GOLDEN, "toy_table.txt"))
             if line.strip() and not line.startswith("#")]
@@ -85,6 +131,17 @@ def _softmax(u, T):
     z = u.astype(np.float64) / np.float64(np.float32(T))
     e = np.exp(z - z.max(axis=-1, keepdims=True))
     return e / e.sum(axis=-1, keepdims=True)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("method", ["spechub", "rrs", "rrsw"])
+@pytest.mark.parametrize("T,lam", [(0.1, 0.7), (0.25, 0.5), (0.5, 0.7)])
+def test_toy_pairs_node_by_node_against_the_oracle(method, T, lam):
+    """The toy workload through the element-wise parity check (V = 50; at T = 0.1 the rows are
+    peaked: a few tokens hold nearly all the mass)."""
+    from parity import check_case
+    wl = W.toy_pairs(T, lam, 96, repeats=4, seed=int(100 * T + 10 * lam), device="cuda:0")
+    check_case(method, wl, seed=int(100 * T))
 
 
 @pytest.mark.gpu
