@@ -42,11 +42,13 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
     if constexpr (LOGITS && NIT == 0) {
         // a streamed logit row: maximum, weights and slab sums in one sweep
         float Z, mq_lane;
+        int mq_chunk = 0;
         cq.s = P.scale_d;
-        swept = sweep_streamed_row<DT, true, 2>(sq, cq.s, sh, phase, mm[0], Z, &mq_lane);
+        swept = sweep_streamed_row<DT, true, 2>(sq, cq.s, sh, phase, mm[0], Z, &mq_lane,
+                                                METHOD == kSpecHub ? &mq_chunk : nullptr);
         if (swept) {
             cq.ms = mm[0] * cq.s;
-            if constexpr (METHOD == kSpecHub) a_virt = block_argmax(sq, mq_lane, mm[0], sh, phase);
+            if constexpr (METHOD == kSpecHub) a_virt = block_argmax_at<DT>(rq, mq_lane, mm[0], mq_chunk, sh, phase);
         }
     }
     if (!swept) {
@@ -123,14 +125,40 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
         if (j == n_ov) ++n_ov;
     };
 
+    // Streamed rows: a token is taken out with the chunk that a load already brought (`raw`, the
+    // chunk of slab s), so that its removal costs no trip to memory of its own
+    auto set_override = [&](int s, float t) {
+        int j = 0;
+        while (j < n_ov && ov_slab[j] != s) ++j;
+        ov_slab[j] = s;
+        ov_val[j] = t;
+        if (j == n_ov) ++n_ov;
+    };
+    auto remove_token_with = [&](int v, int s, const uint4& raw) {
+        excl[n_excl++] = v;
+        float a[E], w[E];
+        finish_chunk<DT>(rq, s * 64 + (int)(threadIdx.x & 63), raw, CV::fill(), a);
+#pragma unroll
+        for (int e = 0; e < E; ++e) w[e] = cq(a[e]);
+        zero_excluded<E>(w, s * 64 + (int)(threadIdx.x & 63), excl, n_excl);
+        set_override(s, wave_sum(chunk_sum<E>(w)));
+    };
+
     int out_tok[MDSD_MAX_K];
     if constexpr (METHOD == kSpecHub) {
+        // streamed rows: the hub's chunk is asked for at once and arrives while the slab sums are searched
+        uint4 hub_raw = make_uint4(0, 0, 0, 0);
+        const int hub_slab = a_virt / (64 * E);
+        if constexpr (NIT == 0) hub_raw = fetch_chunk(rq, hub_slab * 64 + (int)(threadIdx.x & 63));
         const float W = slab_total(rq.nslab, sv);
         const int v = draw(ur[0], W);
         // the mass outside the hub: for the second draw, and for the verify call if it asked
         float W2 = 0.f;
         if (v == a_virt || P.stats_out) {
-            remove_token(a_virt);
+            if constexpr (NIT == 0)
+                remove_token_with(a_virt, hub_slab, hub_raw);
+            else
+                remove_token(a_virt);
             W2 = slab_total(rq.nslab, sv);
             if (P.stats_out && threadIdx.x == 0)
                 P.stats_out[row] = mdsd_row_stats{mm[0], W2, a_virt - rq.head, 0};
@@ -153,12 +181,34 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
             const float W = slab_total(rq.nslab, sv);
             if (i == 0 && P.stats_out && threadIdx.x == 0)  // with replacement: maximum and total mass
                 P.stats_out[row] = mdsd_row_stats{mm[0], W, -1, 0};
-            int v = draw(ur[i], W);
-            if (v < 0) {
-                v = prev;
-                flags |= MDSD_FLAG_Q_EXHAUSTED;
-            } else if (METHOD == kRRSw) {
-                remove_token(v);
+            int v;
+            if constexpr (NIT == 0 && METHOD == kRRSw) {
+                // streamed rows, without replacement: the drawn slab's chunk serves the draw and the
+                // removal of the drawn token
+                SlabHit h{-1, 0.f, 0.f};
+                v = -1;
+                if (icdf_find_slab(rq.nslab, ur[i], W, sv, h)) {
+                    const uint4 raw = fetch_chunk(rq, h.slab * 64 + (int)(threadIdx.x & 63));
+                    float a[E], w[E];
+                    finish_chunk<DT>(rq, h.slab * 64 + (int)(threadIdx.x & 63), raw, CV::fill(), a);
+#pragma unroll
+                    for (int e = 0; e < E; ++e) w[e] = cq(a[e]);
+                    zero_excluded<E>(w, h.slab * 64 + (int)(threadIdx.x & 63), excl, n_excl);
+                    v = icdf_in_slab<E>(w, h);
+                    if (v >= 0) remove_token_with(v, h.slab, raw);
+                }
+                if (v < 0) {
+                    v = prev;
+                    flags |= MDSD_FLAG_Q_EXHAUSTED;
+                }
+            } else {
+                v = draw(ur[i], W);
+                if (v < 0) {
+                    v = prev;
+                    flags |= MDSD_FLAG_Q_EXHAUSTED;
+                } else if (METHOD == kRRSw) {
+                    remove_token(v);
+                }
             }
             prev = v;
             out_tok[i] = v - rq.head;

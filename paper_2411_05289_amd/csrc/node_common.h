@@ -277,6 +277,26 @@ __device__ __forceinline__ int block_argmax(const Src& src, float m_lane, float 
     return a == INT_MAX ? src.r.head : a;  // a row of NaNs has no maximum: stay in bounds
 }
 
+// The same for a streamed row whose sweep remembered, per lane, the first chunk that holds the
+// lane's maximum: the lanes that hold the row's maximum read that one chunk again, instead of
+// streaming their share of the row a second time.
+template <int DT>
+__device__ __forceinline__ int block_argmax_at(const RowView& r, float m_lane, float m_block, int chunk_of_max,
+                                               Shared& sh, int& phase)
+{
+    constexpr int E = Elem<DT>::kPerChunk;
+    int idx = INT_MAX;
+    if (m_lane == m_block) {
+        float a[E];
+        load_chunk<DT>(r, chunk_of_max, -__builtin_inff(), a);
+#pragma unroll
+        for (int e = E - 1; e >= 0; --e)
+            if (a[e] == m_block) idx = chunk_of_max * E + e;
+    }
+    const int a = block_min_index<kWaves>(idx, sh.red, phase);
+    return a == INT_MAX ? r.head : a;  // a row of NaNs has no maximum: stay in bounds
+}
+
 // zero the entries of one chunk whose virtual index is listed in excl
 template <int E>
 __device__ __forceinline__ void zero_excluded(float (&w)[E], int chunk, const int* excl, int n_excl)
@@ -644,7 +664,8 @@ __device__ __forceinline__ void walk_and_verify(const Params& P, VerifyNode veri
 // sums in LDS are in the same units and visible to every wave.
 template <int DT, bool SLABS, int AHEAD = 1, class Src>
 __device__ __forceinline__ bool sweep_streamed_row(const Src& src, float s, Shared& sh, int& phase, float& M,
-                                                   float& Z, float* lane_max_out = nullptr)
+                                                   float& Z, float* lane_max_out = nullptr,
+                                                   int* lane_max_chunk_out = nullptr)
 {
     constexpr int E = Elem<DT>::kPerChunk;
     const int lane = threadIdx.x & 63, wave = wave_id();
@@ -660,18 +681,22 @@ __device__ __forceinline__ bool sweep_streamed_row(const Src& src, float s, Shar
     cw.s = s;
     cw.ms = uniform(r * s);
     float lane_m = ninf, lane_z = 0.f;
-    src.template for_each<AHEAD>([&](int sl, int, const float(&a)[E]) {
+    int lane_m_chunk = 0;  // the first of this lane's chunks that holds lane_m
+    src.template for_each<AHEAD>([&](int sl, int chunk, const float(&a)[E]) {
         float w[E];
+        float cm = a[0];
 #pragma unroll
-        for (int e = 0; e < E; ++e) {
-            lane_m = fmaxf(lane_m, a[e]);
-            w[e] = cw(a[e]);
-        }
+        for (int e = 1; e < E; ++e) cm = fmaxf(cm, a[e]);
+        if (lane_max_chunk_out) lane_m_chunk = cm > lane_m ? chunk : lane_m_chunk;
+        lane_m = fmaxf(lane_m, cm);
+#pragma unroll
+        for (int e = 0; e < E; ++e) w[e] = cw(a[e]);
         const float cs = chunk_sum<E>(w);
         lane_z += cs;
         if constexpr (SLABS) store_slab_sum(sh.slab_w, sl, cs);
     });
     if (lane_max_out) *lane_max_out = lane_m;
+    if (lane_max_chunk_out) *lane_max_chunk_out = lane_m_chunk;
     float mm[1] = {lane_m};
     block_max<kWaves, 1>(mm, sh.red, phase);
     M = mm[0];
