@@ -12,10 +12,16 @@ namespace mdsd {
 // WO (without replacement): q_{i+1} is q without the tokens rejected so far, rescaled by
 // rho_{i+1} = (mass of q) / (mass left); the mass outside all k drafted tokens is summed (positive
 // terms only) in the first pass over the draft row, the masses left are that plus the later drafts'.
+// The first pass over the draft row leaves its first kDraftChunksKept chunks per lane in LDS, so
+// that the passes of later rounds read only the rest of it from memory.
+template <int NIT>
+constexpr int kDraftChunksKept = NIT < 5 ? NIT : 5;
+
 template <int DT, int NIT, bool MASKED, bool WO>
 __device__ __forceinline__ void rrs_resident(const Params& P, const NodeId& id, const RowView& rp,
                                              const RowView& rq, const RowSrc<DT, NIT, MASKED>& sp,
-                                             bool need_full, float* rprob, Shared& sh, int& phase, NodeOut& o)
+                                             bool need_full, float* rprob, Shared& sh,
+                                             uint4 (*q_kept)[kWG], int& phase, NodeOut& o)
 {
     constexpr int E = Elem<DT>::kPerChunk;
     constexpr int HE = E / 2;
@@ -79,15 +85,13 @@ __device__ __forceinline__ void rrs_resident(const Params& P, const NodeId& id, 
         o.outcome = MDSD_BAD_TOKEN;
         return;
     }
-    const float u_last = sh.node_u[k];
-
     float c = 0.f, Wc = 1.f;
     bool decided = false, slabs_current = false;
     int n_rej = 0;
     float rem_k = 0.f;  // WO: unnormalised draft mass outside all k drafted tokens (after the first pass)
     // one pass over both rows: slab sums (and total) of max(p - c_new q, 0), rejected tokens masked;
     // with want_rem also the draft mass outside the drafted tokens
-    auto residual_pass = [&](float c_new, bool want_rem) {
+    auto residual_pass = [&](float c_new, bool want_rem, auto KEPT) {
         const float c_iZq = c_new * iZq;
         // slabs of the first two tokens to mask (with more than two, every slab takes the slow check)
         const int n_mask = want_rem ? k : n_rej;
@@ -101,7 +105,7 @@ __device__ __forceinline__ void rrs_resident(const Params& P, const NodeId& id, 
         int lane_o = threadIdx.x & 63, wave_o = wave_id();
         ExpW cpo = cp;
         asm volatile("" : "+v"(lane_o), "+s"(wave_o), "+s"(cpo.ms));
-        for_each_streamed_at<kStreamAhead>(lane_o, wave_o, sp, rq, ExpW::fill(), [&](int it, int s, int chunk, const uint4& dp, const uint4& dq) {
+        for_each_streamed_cached<1, kDraftChunksKept<NIT>, decltype(KEPT)::value>(lane_o, wave_o, sp, rq, ExpW::fill(), q_kept, [&](int it, int s, int chunk, const uint4& dp, const uint4& dq) {
             float part[2];
             auto half = [&](auto H) {
                 constexpr int hv = decltype(H)::value;
@@ -116,10 +120,10 @@ __device__ __forceinline__ void rrs_resident(const Params& P, const NodeId& id, 
                 if (__builtin_expect(s == s_lo || s == s_hi || n_mask > 2, 0)) {
                     asm volatile("" ::: "memory");
                     for (int j = 0; j < n_mask; ++j) {
-                        const int xvj = sh.node_x[j] + rp.head;
+                        const int off = sh.node_x[j] + rp.head - (chunk * E + hv * HE);
 #pragma unroll
                         for (int e = 0; e < HE; ++e) {
-                            if (chunk * E + hv * HE + e == xvj) {
+                            if (off == e) {
                                 if (j < n_rej) w[e] = 0.f;
                                 eq[e] = 0.f;  // only summed with want_rem, where every drafted token is left out
                             }
@@ -190,7 +194,8 @@ __device__ __forceinline__ void rrs_resident(const Params& P, const NodeId& id, 
         const float c_new = fmaf(Wc, rho, c);
         n_rej = i + 1;
         if (i > 0) __syncthreads();  // earlier readers of the slab sums are done
-        const float W_new = residual_pass(c_new, WO && i == 0);
+        const float W_new = i == 0 ? residual_pass(c_new, WO, std::false_type{})
+                                   : residual_pass(c_new, false, std::true_type{});
         if (W_new > 0.f) {
             c = c_new;
             Wc = W_new;
@@ -209,7 +214,7 @@ __device__ __forceinline__ void rrs_resident(const Params& P, const NodeId& id, 
     if (decided && !need_full) return;
     if (!slabs_current) {
         __syncthreads();
-        residual_pass(c, false);
+        residual_pass(c, false, std::false_type{});  // rare: all of the draft row from memory again
     }
     const float c_iZq = c * iZq;
     auto cw = [&](int s, float(&w)[E]) {
@@ -227,7 +232,7 @@ __device__ __forceinline__ void rrs_resident(const Params& P, const NodeId& id, 
     if (!decided) {
         // (the kernel's first thread writes the outputs: the first wave's draw is the one that counts)
         int v = -1;
-        if (wave_id() == 0) v = icdf_slabs<E>(rp.nslab, u_last, W, sv, cw);
+        if (wave_id() == 0) v = icdf_slabs<E>(rp.nslab, sh.node_u[k], W, sv, cw);
         o.token = v < 0 ? -1 : v - rp.head;
         if (v < 0) o.flags |= MDSD_FLAG_ZERO_RESIDUAL;
     }
@@ -235,7 +240,8 @@ __device__ __forceinline__ void rrs_resident(const Params& P, const NodeId& id, 
 }
 
 template <int DT, int NIT, bool MASKED, bool WO>
-__device__ __forceinline__ NodeOut rrs_node_resident(const Params& P, const NodeId& id, Shared& sh, int& phase)
+__device__ __forceinline__ NodeOut rrs_node_resident(const Params& P, const NodeId& id, Shared& sh,
+                                                     uint4 (*q_kept)[kWG], int& phase)
 {
     const bool need_full = (P.resid_mass != nullptr) || (P.resid_prob != nullptr);
     float* rprob = P.resid_prob ? P.resid_prob + id.row * (int64_t)P.V : nullptr;
@@ -247,7 +253,7 @@ __device__ __forceinline__ NodeOut rrs_node_resident(const Params& P, const Node
         leaf_resident<DT, NIT, MASKED, false>(P, rp, sp, P.u[id.row * (P.k + 1) + P.k], rprob, sh, phase, o);
     } else {
         const RowView rq = make_row<DT>(P.draft, P.ld_d, id.row, P.V);
-        rrs_resident<DT, NIT, MASKED, WO>(P, id, rp, rq, sp, need_full, rprob, sh, phase, o);
+        rrs_resident<DT, NIT, MASKED, WO>(P, id, rp, rq, sp, need_full, rprob, sh, q_kept, phase, o);
     }
     write_node_outputs(P, id, o.outcome, o.token, o.rmass, o.flags);
     return o;
@@ -257,8 +263,9 @@ template <int DT, int NIT, bool MASKED, bool WO>
 __global__ __launch_bounds__(kWG, (NIT <= 8 ? kStatsWavesPerSimd : 2)) void rrs_verify_resident(const Params P)
 {
     __shared__ Shared sh;
+    __shared__ uint4 q_kept[kDraftChunksKept<NIT>][kWG];
     int phase = 0;
-    rrs_node_resident<DT, NIT, MASKED, WO>(P, node_of_block(P), sh, phase);
+    rrs_node_resident<DT, NIT, MASKED, WO>(P, node_of_block(P), sh, q_kept, phase);
 }
 
 // which shapes the RRS kernel for rows in registers is built for (the others would spill or run

@@ -316,6 +316,55 @@ __device__ __forceinline__ void for_each_streamed_at(int lane, int wave, const R
     }
 }
 
+// f(integral_constant<int, 0>), ..., f(integral_constant<int, N - 1>)
+template <int N, int I = 0, class F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<N, I + 1>(f);
+    }
+}
+
+// The same pass with the first QC chunks of row b kept in LDS between passes: a pass with
+// CACHED = false reads all of b from memory and leaves those chunks in `cache` (one 16-byte
+// entry per thread and chunk, read and written by that thread only: no barrier), a pass with
+// CACHED = true takes them from there and reads only the rest of b from memory.
+template <int QW, int QC, bool CACHED, int DT, int NIT, bool MASKED, class Body>
+__device__ __forceinline__ void for_each_streamed_cached(int lane, int wave, const RowSrc<DT, NIT, MASKED>& sa,
+                                                         const RowView& rb, float fill_b, uint4 (*cache)[kWG],
+                                                         Body body)
+{
+    static_assert(NIT > 0 && QW == 1 && QC <= NIT, "row a must be resident, one chunk ahead");
+    const uint32_t fb = __builtin_bit_cast(uint32_t, fill_b);
+    const uint32_t fw = DT == 0 ? fb : ((fb >> 16) | (fb & 0xffff0000u));
+    const int tid = wave * 64 + lane;
+    auto fetch = [&](auto IT) {
+        constexpr int it = decltype(IT)::value;
+        if constexpr (CACHED && it < QC) {
+            return cache[it][tid];
+        } else {
+            const int chunk = (it * kWaves + wave) * 64 + lane;
+            return load16(rb.chunks, chunk < rb.nchunk ? chunk : rb.nchunk - 1);
+        }
+    };
+    uint4 nxt = fetch(std::integral_constant<int, 0>{});
+    static_for<NIT>([&](auto IT) {
+        constexpr int it = decltype(IT)::value;
+        const int s = it * kWaves + wave;
+        uint4 cur = nxt;
+        if constexpr (it + 1 < NIT) nxt = fetch(std::integral_constant<int, it + 1>{});
+        if (s < sa.r.nslab) {
+            if ((s + 1) * 64 > rb.nchunk) {  // the row's last slab, not full
+                if (s * 64 + lane >= rb.nchunk) cur = make_uint4(fw, fw, fw, fw);
+            }
+            if constexpr (!CACHED && it < QC) cache[it][tid] = cur;
+            body(it, s, s * 64 + lane, sa.d[it], cur);
+        }
+        __builtin_amdgcn_sched_barrier(0);  // one chunk pair at a time
+    });
+}
+
 // store one slab's sum: every lane passes its chunk sum, lane 63 writes
 __device__ __forceinline__ void store_slab_sum(float* slab_w, int s, float lane_sum)
 {
