@@ -3,8 +3,8 @@
 
 A step = one pass of the whole path over one batch of synthetic token trees:
 spechub_draft (pair sampling for every internal node), spechub_verify (every
-node) and the tree walk, which the verify kernel runs itself (two launches per
-step; --separate-walk makes the walk a third launch).  Inputs are resident in HBM; the step rotates over
+node) and the tree walk, which the verify kernel runs itself at this batch size
+(two launches per step; a third launch for large batches, see --separate-walk).  Inputs are resident in HBM; the step rotates over
 several distinct copies of the batch so that the working set exceeds the
 256 MiB Infinity Cache and "HBM GB/s" is not cache bandwidth.
 
@@ -53,8 +53,11 @@ def parse():
                     help="spechub_verify recomputes the draft row's hub and normalisers instead of "
                          "taking them from spechub_draft")
     ap.add_argument("--separate-walk", action="store_true",
-                    help="three launches per step (draft, verify, walk) instead of two (the verify kernel "
-                         "walks each tree itself when the tree's last node is done)")
+                    help="three launches per step (draft, verify, walk) whatever the batch size")
+    ap.add_argument("--walk-in-verify", action="store_true",
+                    help="two launches per step whatever the batch size: the verify kernel walks each tree "
+                         "itself when the tree's last node is done (the default up to "
+                         "binding.WALK_IN_VERIFY_MAX_NODES tree nodes per batch, three launches beyond)")
     ap.add_argument("--graph", action="store_true",
                     help="replay one HIP graph per step instead of launching its three kernels one by one "
                          "(measured slower on this workload: 63.9 against 59.8 us per step)")
@@ -128,7 +131,12 @@ def main():
         if toy:
             repeats = max(1, args.batch // 200) if args.batch > 0 else 512
             return W.toy_pairs(0.25, 0.7, 200, repeats=repeats, seed=seed, device=dev)
-        return W.config(args.config, device=dev, seed=seed, **over)
+        w = W.config(args.config, device=dev, seed=seed, **over)
+        if args.batch > 0 and "_B%d_" % args.batch not in w.name:
+            # another batch size than the configuration's: its own name, so that no profile
+            # summary of the configuration's own size is taken for it
+            w.name += "@B=%d" % args.batch
+        return w
 
     wl0 = make_workload(args.seed)
     alg_bytes = wl0.algorithmic_bytes()
@@ -143,7 +151,13 @@ def main():
     plans = [B.StepPlan(args.method, pbs[i], u_d[i], u_v[i], hand_stats=not args.no_stats) for i in range(copies)]
     stream = B._stream()
 
-    fused = not args.separate_walk
+    # where the tree walk runs: inside the verify kernel (two launches per step) or as a launch
+    # of its own (three); by default the binding's rule by batch size decides
+    fused = plans[0].walk_in_verify
+    if args.separate_walk:
+        fused = False
+    if args.walk_in_verify:
+        fused = True
 
     def step(i, ev=None):
         pl = plans[i % copies]

@@ -335,12 +335,24 @@ def tree_walk(pb: Problem, outcome, token, accept_depth=None, emitted=None):
     return ad, em
 
 
+# Up to this many tree nodes per batch, StepPlan.run() lets the verify kernel walk the trees
+# itself (two launches per step).  The arrival count keeps a finished workgroup about a
+# microsecond longer on its compute unit, which costs more than the walk's own launch
+# (2-3 us) once a batch is several times what the chip holds at once: measured on one MI355X,
+# 31-node trees at V = 32000: B = 16 27.3 against 29.0 us per step, B = 64 54.9 against 55.6,
+# B = 256 171.1 against 165.6, B = 1024 632 against 605.
+WALK_IN_VERIFY_MAX_NODES = 4096
+
+
 class StepPlan:
     """Marshalled arguments of one draft + verify + walk step, so that a serving loop pays
-    three foreign calls per step and nothing else.  The tensors handed in must stay alive
-    and in place for the life of the plan."""
+    two or three foreign calls per step and nothing else.  The tensors handed in must stay
+    alive and in place for the life of the plan.  walk_in_verify: True = the verify kernel
+    walks the trees (one launch), False = mdsd_tree_walk as a launch of its own, None = by
+    batch size (WALK_IN_VERIFY_MAX_NODES)."""
 
-    def __init__(self, method: str, pb: Problem, u_draft, u_verify, *, flags=True, hand_stats=True):
+    def __init__(self, method: str, pb: Problem, u_draft, u_verify, *, flags=True, hand_stats=True,
+                 walk_in_verify=None):
         if method not in ("spechub", "rrs", "rrsw"):
             raise ValueError("unknown method %r" % method)
         if hand_stats and pb.draft_stats is None:
@@ -348,6 +360,7 @@ class StepPlan:
         B, N, _ = pb.draft.shape
         dev = pb.draft.device
         self.method, self.pb = method, pb
+        self.walk_in_verify = (B * N <= WALK_IN_VERIFY_MAX_NODES) if walk_in_verify is None else bool(walk_in_verify)
         self._cp = _c_problem(pb)
         _check_dev(u_draft, "u_draft", torch.float32, (B, N, pb.k))
         _check_dev(u_verify, "u_verify", torch.float32, (B, N, pb.k + 1))
@@ -426,7 +439,11 @@ class StepPlan:
     def run(self, stream=None):
         st = _stream() if stream is None else stream
         self.draft(st)
-        self.verify_and_walk(st)
+        if self.walk_in_verify:
+            self.verify_and_walk(st)
+        else:
+            self.verify(st)
+            self.walk(st)
         return self.out
 
 

@@ -513,6 +513,34 @@ def test_bitwise_reproducible():
         assert torch.equal(v1[key], v2[key]), key
 
 
+# ----------------------------------------------------------------- the marshalled step bench.py times
+@pytest.mark.parametrize("method", ALL)
+def test_step_plan_gives_what_the_separate_calls_give(method):
+    """StepPlan.run() (the launches bench.py times) with the walk in the verify kernel, as a launch
+    of its own and by the batch-size rule, run twice each on one plan, against draft, verify and
+    walk called one by one through the allocating binding."""
+    wl = W.config(3, device=DEV, B=12, V=9000, seed=11)
+    pb = B.Problem.from_workload(wl).with_draft_stats()   # the plan hands the draft call's records to verify
+    u_d, u_v = uniforms(wl, 5)
+    want_d = DRAFT[method](pb, u_d)
+    want = VERIFY[method](pb, want_d["tokens"], u_v, flags=True, walk=True)
+    for placement in (True, False, None):
+        plan = B.StepPlan(method, pb, u_d, u_v, walk_in_verify=placement)
+        assert plan.walk_in_verify == (True if placement is None else placement)   # 12 * 31 nodes: a small batch
+        for rep in range(2):
+            for t in plan.out.values():
+                if t is not None:
+                    t.fill_(-9)
+            out = plan.run()
+            torch.cuda.synchronize()
+            assert torch.equal(plan.tokens, want_d["tokens"]), (placement, rep)
+            for key in ("outcome", "token", "flags", "accept_depth", "emitted"):
+                assert torch.equal(out[key], want[key]), (placement, rep, key)
+    big = B.Problem.from_workload(W.config(3, device=DEV, B=160, V=1000, seed=1))
+    u_d, u_v = uniforms(W.config(3, device=DEV, B=160, V=1000, seed=1), 5)
+    assert B.StepPlan(method, big, u_d, u_v).walk_in_verify is False   # 160 * 31 nodes: beyond the rule
+
+
 # ----------------------------------------------------------------- Monte-Carlo tokens/step
 @pytest.mark.parametrize("method", ALL)
 def test_tokens_per_step_within_3_sigma(method, request):
