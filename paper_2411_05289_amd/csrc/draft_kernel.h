@@ -4,7 +4,7 @@
 #pragma once
 #include "launch.h"
 
-namespace mdsd {
+namespace MDSD_NS {
 
 // ---------------------------------------------------------------- draft kernel
 template <int DT, bool LOGITS, int METHOD, int NIT, bool MASKED = true>
@@ -259,4 +259,4 @@ static void launch_draft_method(int dtype, bool logits, int nit, bool masked, di
     }
 }
 
-}  // namespace mdsd
+}  // namespace MDSD_NS

@@ -3,7 +3,7 @@
 #pragma once
 #include "node_common.h"
 
-namespace mdsd {
+namespace MDSD_NS {
 
 // spechub_resident.hip: SpecHub on logit rows that fit in registers (nit = 4, 8 or 16 chunks
 // per lane); path = one workgroup per tree
@@ -31,4 +31,4 @@ void launch_draft_rrs(int dtype, bool logits, int nit, bool masked, dim3 grid, d
 void launch_draft_rrsw(int dtype, bool logits, int nit, bool masked, dim3 grid, dim3 block, hipStream_t st,
                        const Params& P);
 
-}  // namespace mdsd
+}  // namespace MDSD_NS

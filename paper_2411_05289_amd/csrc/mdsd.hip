@@ -3,6 +3,7 @@
 // draft_*.hip; the device code they share is in node_common.h), the tree walk and Philox
 // kernels, and the C entry points.
 #include "launch.h"
+#include "launch_wave.h"
 
 #include <atomic>
 
@@ -131,6 +132,14 @@ static int resident_chunks(const mdsd_problem* pb)
     if (per_lane <= 16) return 16;
     return 0;
 }
+// Vocabularies of a few hundred tokens: one wavefront per node (the 64-thread build of the generic
+// kernels) instead of one 512-thread workgroup, most of whose wavefronts would hold no part of the row
+static bool row_fits_one_wave(const mdsd_problem* pb)
+{
+    const int per_chunk = pb->dtype == MDSD_FP32 ? 4 : 8;
+    const int64_t nchunk = ((int64_t)pb->V + 2 * per_chunk - 2) / per_chunk;
+    return nchunk <= mdsd_wave::kWaveBuildMaxChunks;
+}
 // true when some element of some row may need masking: a row that does not start on a
 // 16-byte boundary, or a vocabulary that is not a whole number of 16-byte chunks
 static bool rows_need_mask(const mdsd_problem* pb)
@@ -159,6 +168,10 @@ static void launch_verify(int method, const mdsd_problem* pb, const Params& P, b
     const bool lg = pb->kind == MDSD_LOGITS;
     int nit = resident_chunks(pb);
     const dim3 grid = path ? dim3((unsigned)P.B) : node_grid(P, nit), block(kWG);
+    if (row_fits_one_wave(pb)) {
+        mdsd_wave::launch_verify(method, pb->dtype, lg, path, grid, st, P);
+        return;
+    }
     if (method == kSpecHub && lg && nit > 0) {
         launch_spechub_resident(pb->dtype, nit, rows_need_mask(pb), path, grid, block, st, P);
         return;
@@ -186,6 +199,10 @@ static void launch_draft(int method, const mdsd_problem* pb, const Params& P, hi
     const bool lg = pb->kind == MDSD_LOGITS;
     const int nit = resident_chunks(pb);
     const dim3 grid = node_grid(P, nit), block(kWG);
+    if (row_fits_one_wave(pb)) {
+        mdsd_wave::launch_draft(method, pb->dtype, lg, grid, st, P);
+        return;
+    }
     const int es = pb->dtype == MDSD_FP32 ? 4 : 2;
     const bool masked = ((uintptr_t)pb->draft & 15) || ((pb->ld_d * es) & 15) || (pb->V % (16 / es));
     if (method == kSpecHub)
@@ -435,6 +452,6 @@ const char* mdsd_strerror(int code)
     }
 }
 
-int mdsd_version(void) { return 103; }
+int mdsd_version(void) { return 104; }
 
 }  // extern "C"

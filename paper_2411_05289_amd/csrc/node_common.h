@@ -22,10 +22,11 @@
 #include <stdint.h>
 
 #include "mdsd.h"
+#include "params.h"
 #include "resident.h"
 #include "scan_core.h"
 
-namespace mdsd {
+namespace MDSD_NS {
 
 enum Method { kSpecHub = 0, kRRS = 1, kRRSw = 2 };
 
@@ -36,35 +37,7 @@ enum Method { kSpecHub = 0, kRRS = 1, kRRSw = 2 };
 constexpr int kStreamAhead = 1;
 constexpr int kStatsWavesPerSimd = 6;
 
-struct Params {
-    const void* target;
-    const void* draft;
-    int64_t ld_t, ld_d;
-    float temp_target, temp_draft;
-    // log2(e) / temperature, formed once on the host: the correctly rounded quotient, which the
-    // kernels would otherwise each compute again with a dozen instructions per wave
-    float scale_t, scale_d;
-    int B, N, V, k, depth, n_internal;
-    const int32_t* first_child;
-    const int32_t* tokens;
-    const float* u;
-    int32_t* outcome;
-    int32_t* token;
-    float* resid_mass;
-    int32_t* flags;
-    float* resid_prob;
-    int32_t* accept_depth;  // path-only kernels, and the full kernels when they walk the trees themselves
-    int32_t* emitted;
-    // full verify kernels with the walk inside: one arrival counter per tree (all zero when the
-    // kernel starts, all zero again when it ends); nullptr = the walk is a launch of its own
-    int32_t* tree_count;
-    // draft kernels
-    int32_t* tokens_out;
-    int32_t* hub_out;
-    // draft-row statistics: written by the SpecHub draft kernel, read by the SpecHub verify kernel
-    mdsd_row_stats* stats_out;
-    const mdsd_row_stats* stats_in;
-};
+using ::mdsd::Params;
 
 struct Shared {
     BlockScratch<kWaves> red;
@@ -719,4 +692,4 @@ __device__ __forceinline__ bool sweep_streamed_row(const Src& src, float s, Shar
     return ok;
 }
 
-}  // namespace mdsd
+}  // namespace MDSD_NS

@@ -5,7 +5,7 @@
 
 #include "scan_core.h"
 
-namespace mdsd {
+namespace MDSD_NS {
 
 // register chunk `it` of this lane, `it` known only at run time
 template <int NIT>
@@ -48,4 +48,4 @@ __device__ __forceinline__ float own_element(const RowSrc<DT, NIT, MASKED>& src,
     return x;
 }
 
-}  // namespace mdsd
+}  // namespace MDSD_NS

@@ -6,9 +6,11 @@
 // row and the elements behind its end are masked, never used.
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include "build_config.h"
 #include <stdint.h>
 
-namespace mdsd {
+namespace MDSD_NS {
 
 template <int DT> struct Elem;
 template <> struct Elem<0> {  // fp32
@@ -126,4 +128,4 @@ __device__ __forceinline__ void load_chunk(const RowView& r, int chunk, float fi
     finish_chunk<DT>(r, chunk, fetch_chunk(r, chunk), fill, v);
 }
 
-}  // namespace mdsd
+}  // namespace MDSD_NS

@@ -13,14 +13,11 @@
 #include "row_io.h"
 #include "wave_ops.h"
 
-namespace mdsd {
+namespace MDSD_NS {
 
-#ifndef MDSD_WG
-#define MDSD_WG 512
-#endif
 constexpr int kWG = MDSD_WG;
 constexpr int kWaves = kWG / kWave;
-constexpr int kMaxSlabs = 2048;
+constexpr int kMaxSlabs = MDSD_MAX_SLABS;
 constexpr float kLog2e = 1.44269504088896340736f;
 
 // stored element -> unnormalised probability.  Logits: 2^(l*s - ms) with
@@ -499,4 +496,4 @@ __device__ __forceinline__ int icdf_slabs(int nslab, float u, float W, SlabVal s
     return icdf_in_slab<E>(w, h);
 }
 
-}  // namespace mdsd
+}  // namespace MDSD_NS

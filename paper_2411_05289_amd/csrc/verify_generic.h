@@ -4,7 +4,7 @@
 #pragma once
 #include "launch.h"
 
-namespace mdsd {
+namespace MDSD_NS {
 
 // The softmax scales arrive in scalar registers.  The streamed passes of the SpecHub form of this
 // kernel measured 4 % slower with the scale as a scalar operand of their multiply-adds than with
@@ -76,6 +76,9 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
             if (!q_asked) sq.init(rq, CV::fill());
             q_asked = true;
         };
+        // one wavefront per node: the rows are a few hundred bytes and every trip to memory is a
+        // quarter of the node's life, so the draft row is asked for together with the target row
+        if constexpr (kWaves == 1) need_q();
         const int32_t* xt = P.tokens + (int64_t)id.b * P.N + id.c0;
         CV cp{0.f, 0.f}, cq{0.f, 0.f};
 
@@ -556,4 +559,4 @@ static void launch_verify_generic(int dtype, bool logits, int nit, bool path, di
     }
 }
 
-}  // namespace mdsd
+}  // namespace MDSD_NS

@@ -4,9 +4,11 @@
 // bit-reproducible from launch to launch.
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include "build_config.h"
 #include <limits.h>
 
-namespace mdsd {
+namespace MDSD_NS {
 
 constexpr int kWave = 64;
 
@@ -171,4 +173,4 @@ __device__ __forceinline__ int block_min_index(int idx, BlockScratch<WAVES>& s, 
     return r;
 }
 
-}  // namespace mdsd
+}  // namespace MDSD_NS

@@ -227,8 +227,16 @@ def test_rows_masked_down_to_a_few_tokens(method, V, K, request):
 # ----------------------------------------------------------------- every dispatched kernel variant
 # (dtype, kind, V, row offset in elements): between them these reach every instantiation the
 # launchers can choose: rows in registers with 4, 8 or 16 chunks per lane, with and without masked
-# first / last chunks, fp32 and bf16, logits and probabilities, and the streamed forms.
+# first / last chunks, fp32 and bf16, logits and probabilities, the streamed forms, and the
+# one-wavefront-per-node build that takes rows of up to 256 16-byte chunks.
 _VARIANTS = [
+    ("fp32", "logits", 1000, 0),     # one wavefront per node: fp32 logits, four chunks per lane
+    ("fp32", "logits", 301, 1),      # ... masked
+    ("bf16", "logits", 2040, 0),     # ... bf16 logits, the longest row of that build
+    ("bf16", "logits", 777, 3),      # ... masked
+    ("fp32", "probs", 513, 0),       # ... fp32 probabilities
+    ("bf16", "probs", 2042, 0),      # the shortest row of the 512-thread build: bf16 probabilities
+    ("fp32", "logits", 1021, 0),     # ... fp32 logits
     ("fp32", "logits", 12000, 0),    # fp32, 8 chunks per lane, no masking
     ("fp32", "logits", 12001, 0),    # ... masked (ld = V is odd: rows start on every 4-byte phase)
     ("fp32", "logits", 30000, 1),    # fp32, 16 chunks per lane, masked (base one element off)
@@ -237,7 +245,7 @@ _VARIANTS = [
     ("bf16", "logits", 50304, 0),    # bf16, 16 chunks per lane, no masking
     ("bf16", "logits", 50257, 0),    # ... masked
     ("bf16", "logits", 65520, 0),    # the longest row that stays in registers
-    ("bf16", "probs", 1000, 0),      # bf16 probabilities: registers
+    ("bf16", "probs", 1000, 0),      # bf16 probabilities: one wavefront per node
     ("bf16", "probs", 4099, 3),      # ... masked
     ("bf16", "probs", 40000, 0),     # ... 16 chunks per lane / streamed
     ("bf16", "probs", 70016, 0),     # ... streamed
@@ -315,11 +323,12 @@ def test_first_child_entries_that_cannot_be_children_count_as_leaves():
             assert torch.equal(res[0][key], res[1][key]), (bad, key)
 
 
+@pytest.mark.parametrize("V", [600, 4000], ids=["wave_per_node", "workgroup_per_node"])
 @pytest.mark.parametrize("method", ALL)
-def test_trees_of_more_than_64_nodes(method, request):
+def test_trees_of_more_than_64_nodes(method, V, request):
     """127-node trees: the walk (as a launch of its own and inside the verify kernel) goes node
     by node from memory instead of holding the tree in one wavefront's lanes."""
-    wl = W.config(3, device=DEV, B=5, V=600, depth=7, seed=61)
+    wl = W.config(3, device=DEV, B=5, V=V, depth=7, seed=61)
     assert wl.N == 127
     note(request, check_case(method, wl, seed=61, full_outputs=False))
 
