@@ -12,7 +12,13 @@
 #ifndef MDSD_NS
 #define MDSD_NS mdsd
 #endif
-// slab sums a workgroup keeps in LDS: bounds the vocabulary (64 chunks of 16 bytes per slab)
+// nodes that share a workgroup (each with MDSD_WG threads of its own); more than one only with
+// MDSD_WG == 64: the dispatcher starts about four times as many wavefronts per second in
+// workgroups of four as in workgroups of one
+#ifndef MDSD_NODES_PER_WG
+#define MDSD_NODES_PER_WG 1
+#endif
+// slab sums a node keeps in LDS: bounds the vocabulary (64 chunks of 16 bytes per slab)
 #ifndef MDSD_MAX_SLABS
 #define MDSD_MAX_SLABS 2048
 #endif

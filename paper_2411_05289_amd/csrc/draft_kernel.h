@@ -8,19 +8,21 @@ namespace MDSD_NS {
 
 // ---------------------------------------------------------------- draft kernel
 template <int DT, bool LOGITS, int METHOD, int NIT, bool MASKED = true>
-__global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
+__global__ __launch_bounds__(kWG * kNodesPerWG) void draft_kernel(const Params P)
 {
     constexpr int E = Elem<DT>::kPerChunk;
     using CV = ToWeight<LOGITS>;
-    __shared__ Shared sh;
+    __shared__ Shared shs[kNodesPerWG];
+    Shared& sh = shs[node_slot()];
     int phase = 0;
-    // one workgroup per node; a leaf only records that it has no hub
+    // one group of kWG threads per node; a leaf only records that it has no hub
     const NodeId id = node_of_block(P);
+    if (id.b < 0) return;
     const int b = id.b, n = id.n, c0 = id.c0;
     const int64_t row = id.row;
-    if (n == 0 && threadIdx.x == 0) P.tokens_out[(int64_t)b * P.N] = -1;
+    if (n == 0 && node_thread() == 0) P.tokens_out[(int64_t)b * P.N] = -1;
     if (c0 < 0) {
-        if (threadIdx.x == 0) {
+        if (node_thread() == 0) {
             if (P.hub_out) P.hub_out[row] = -1;
             if (P.flags) P.flags[row] = 0;
             if (P.stats_out) P.stats_out[row] = mdsd_row_stats{0.f, 0.f, -1, 0};
@@ -64,7 +66,7 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
         }
         pass_weights_to_slabs<CV>(sq, cq, nullptr, 0, sh.slab_w);
     }
-    __syncthreads();
+    node_barrier();
 
     // slab sums with some tokens removed: only the slabs holding a removed token change,
     // and those are recomputed with the tokens masked (never by subtraction)
@@ -94,7 +96,7 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
         if constexpr (NIT > 0) {
             // draws with replacement follow each other with no barrier in between: the result
             // slot in LDS must have been read by every wave before the next draw writes it
-            if constexpr (METHOD == kRRS) __syncthreads();
+            if constexpr (METHOD == kRRS) node_barrier();
             return __builtin_amdgcn_readfirstlane(draw_resident<E>(rq.nslab, u, W, sv, cw_reg, sh));
         } else {
             return icdf_slabs<E>(rq.nslab, u, W, sv, cw);
@@ -111,7 +113,7 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
                 const float ts = wave_sum(chunk_sum<E>(w));
                 if ((threadIdx.x & 63) == 0) sh.bcast_f = ts;
             }
-            __syncthreads();
+            node_barrier();
             t = sh.bcast_f;
         } else {
             float w[E];
@@ -160,7 +162,7 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
             else
                 remove_token(a_virt);
             W2 = slab_total(rq.nslab, sv);
-            if (P.stats_out && threadIdx.x == 0)
+            if (P.stats_out && node_thread() == 0)
                 P.stats_out[row] = mdsd_row_stats{mm[0], W2, a_virt - rq.head, 0};
         }
         if (v != a_virt) {
@@ -179,7 +181,7 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
         int prev = rq.head;
         for (int i = 0; i < k; ++i) {
             const float W = slab_total(rq.nslab, sv);
-            if (i == 0 && P.stats_out && threadIdx.x == 0)  // with replacement: maximum and total mass
+            if (i == 0 && P.stats_out && node_thread() == 0)  // with replacement: maximum and total mass
                 P.stats_out[row] = mdsd_row_stats{mm[0], W, -1, 0};
             int v;
             if constexpr (NIT == 0 && METHOD == kRRSw) {
@@ -214,7 +216,7 @@ __global__ __launch_bounds__(kWG) void draft_kernel(const Params P)
             out_tok[i] = v - rq.head;
         }
     }
-    if (threadIdx.x == 0) {
+    if (node_thread() == 0) {
         for (int i = 0; i < k; ++i) xt[i] = out_tok[i];
         if (P.hub_out) P.hub_out[row] = (METHOD == kSpecHub) ? a_virt - rq.head : -1;
         if (P.flags) P.flags[row] = flags;

@@ -1,6 +1,6 @@
 // Launchers of the one-wavefront-per-node build of the generic kernels (wave_*.hip): for rows of at
-// most kWaveBuildMaxChunks 16-byte chunks.  Same arguments as the launchers of the main build;
-// workgroups are 64 threads, one per node (path: one per tree).
+// most kWaveBuildMaxChunks 16-byte chunks.  A workgroup is one or several wavefronts, each with a
+// node of its own (path: a tree of its own); the launchers size the grid from the problem.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -12,6 +12,6 @@ namespace mdsd_wave {
 constexpr int kWaveBuildMaxChunks = 4 * 64;
 
 void launch_verify(int method, int dtype, bool logits, bool path, dim3 grid, hipStream_t st, const mdsd::Params& P);
-void launch_draft(int method, int dtype, bool logits, dim3 grid, hipStream_t st, const mdsd::Params& P);
+void launch_draft(int method, int dtype, bool logits, hipStream_t st, const mdsd::Params& P);
 
 }  // namespace mdsd_wave

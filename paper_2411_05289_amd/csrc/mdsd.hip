@@ -200,7 +200,7 @@ static void launch_draft(int method, const mdsd_problem* pb, const Params& P, hi
     const int nit = resident_chunks(pb);
     const dim3 grid = node_grid(P, nit), block(kWG);
     if (row_fits_one_wave(pb)) {
-        mdsd_wave::launch_draft(method, pb->dtype, lg, grid, st, P);
+        mdsd_wave::launch_draft(method, pb->dtype, lg, st, P);
         return;
     }
     const int es = pb->dtype == MDSD_FP32 ? 4 : 2;

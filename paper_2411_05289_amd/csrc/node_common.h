@@ -90,6 +90,13 @@ __device__ __forceinline__ NodeId node_of_item(const Params& P, int w)
 // dimension (gridDim.y == 1) and take the division.
 __device__ __forceinline__ NodeId node_of_block(const Params& P)
 {
+    if constexpr (kNodesPerWG > 1) {
+        // several nodes per workgroup, numbered in one dimension; a slot past the last node has
+        // none (b = -1) and its wavefront leaves at once
+        const int64_t w = (int64_t)blockIdx.x * kNodesPerWG + node_slot();
+        if (w >= (int64_t)P.B * P.N) return NodeId{-1, -1, -1, -1};
+        return node_of_item(P, (int)w);
+    }
     if (gridDim.y == 1) return node_of_item(P, blockIdx.x);
     NodeId id;
     // Workgroup i of a launch runs on XCD i mod 8, and with the tree as the fast index that would
@@ -184,8 +191,8 @@ __device__ __forceinline__ void wave_walk(const int32_t* outcome, const int32_t*
 __device__ __forceinline__ void write_node_outputs(const Params& P, const NodeId& id, int outcome, int token,
                                                    float rmass, int flags)
 {
-    if (threadIdx.x >= kWave) return;
-    const bool first = threadIdx.x == 0;
+    if (node_thread() >= kWave) return;
+    const bool first = node_thread() == 0;
     if (first) {
         if (P.resid_mass) P.resid_mass[id.row] = rmass;
         if (P.flags) P.flags[id.row] = flags;
@@ -450,7 +457,7 @@ __device__ __forceinline__ int draw_resident(int nslab, float u, float W, SlabVa
         const int v = icdf_in_slab<E>(w, h);
         if ((threadIdx.x & 63) == 0) sh.bcast_i = v;
     }
-    __syncthreads();
+    node_barrier();
     return sh.bcast_i;
 }
 
@@ -509,7 +516,7 @@ __device__ __forceinline__ RowNorm wave_shifted_norm(const Src& sp, float s, flo
         sh.red.buf[phase][wave][1] = zw;
     }
     if constexpr (SLABS) sums.store(sh.slab_w, sp.r.nslab);
-    __syncthreads();
+    node_barrier();
     float ms = sh.red.buf[phase][0][0];
 #pragma unroll
     for (int w = 1; w < kWaves; ++w) ms = fmaxf(ms, sh.red.buf[phase][w][0]);
@@ -549,7 +556,7 @@ __device__ __forceinline__ void leaf_resident(const Params& P, const RowView& rp
     if constexpr (Src::kHasShiftEstimate) {
         W = slab_sums(sp.lane_shift_estimate());
         if (__builtin_expect(!(W > 0.f && W < __builtin_inff()), 0)) {
-            __syncthreads();  // every wave has read the slab sums that are about to be rewritten
+            node_barrier();  // every wave has read the slab sums that are about to be rewritten
             W = slab_sums(lane_max(sp));
         }
     } else {
@@ -588,8 +595,9 @@ __device__ __forceinline__ float uniform(float v) { return as_f(__builtin_amdgcn
 template <class VerifyNode>
 __device__ __forceinline__ void walk_and_verify(const Params& P, VerifyNode verify_node)
 {
-    const int b = blockIdx.x;
-    for (int i = threadIdx.x; i < P.N; i += kWG) {
+    const int b = (int)blockIdx.x * kNodesPerWG + node_slot();
+    if (b >= P.B) return;
+    for (int i = node_thread(); i < P.N; i += kWG) {
         const int64_t r = (int64_t)b * P.N + i;
         P.outcome[r] = MDSD_UNVISITED;
         P.token[r] = -1;
@@ -597,10 +605,10 @@ __device__ __forceinline__ void walk_and_verify(const Params& P, VerifyNode veri
         if (P.resid_mass) P.resid_mass[r] = 0.f;
     }
     int32_t* em = P.emitted + (int64_t)b * P.depth;
-    for (int i = threadIdx.x; i < P.depth; i += kWG) em[i] = -1;
+    for (int i = node_thread(); i < P.depth; i += kWG) em[i] = -1;
     // the visited nodes' entries are rewritten below by another thread of this workgroup
     __threadfence_block();
-    __syncthreads();
+    node_barrier();
     int n = 0, d = 0;
     for (;;) {
         NodeId id;
@@ -616,13 +624,13 @@ __device__ __forceinline__ void walk_and_verify(const Params& P, VerifyNode veri
         id.row = (int64_t)b * P.N + n;
         const NodeOut o = verify_node(id);
         const int outcome = uniform(o.outcome), token = uniform(o.token);
-        if (threadIdx.x == 0 && d < P.depth) em[d] = token;
+        if (node_thread() == 0 && d < P.depth) em[d] = token;
         if (id.c0 < 0 || outcome < 0 || outcome >= P.k || d + 1 >= P.depth) break;
         n = id.c0 + outcome;
         ++d;
-        __syncthreads();  // the next node reuses the LDS areas of this one
+        node_barrier();  // the next node reuses the LDS areas of this one
     }
-    if (threadIdx.x == 0) P.accept_depth[b] = d;
+    if (node_thread() == 0) P.accept_depth[b] = d;
 }
 
 // One sweep over a logit row that is streamed from memory (too long for registers), instead of
@@ -687,7 +695,7 @@ __device__ __forceinline__ bool sweep_streamed_row(const Src& src, float s, Shar
         if (ok) {
             for (int i = wave + kWaves * lane; i < src.r.nslab; i += kWaves * 64) sh.slab_w[i] *= scale;
         }
-        __syncthreads();
+        node_barrier();
     }
     return ok;
 }

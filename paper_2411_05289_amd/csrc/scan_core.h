@@ -15,8 +15,6 @@
 
 namespace MDSD_NS {
 
-constexpr int kWG = MDSD_WG;
-constexpr int kWaves = kWG / kWave;
 constexpr int kMaxSlabs = MDSD_MAX_SLABS;
 constexpr float kLog2e = 1.44269504088896340736f;
 

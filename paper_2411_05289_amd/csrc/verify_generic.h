@@ -55,7 +55,7 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                 cp.ms = mm[0] * cp.s;
             }
             pass_weights_to_slabs<CV>(sp, cp, nullptr, 0, sh.slab_w);
-            __syncthreads();
+            node_barrier();
         }
         float W;
         const int v = draw_from_row<DT, CV>(rp, cp, nullptr, 0, sh.slab_w, ur[k], W);
@@ -217,7 +217,7 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                 if (degenerate) {
                     // residual of the single-draft case: p with the hub removed
                     pass_weights_to_slabs<CV>(sp, cp, &a_virt, 1, sh.slab_w);
-                    __syncthreads();
+                    node_barrier();
                     float W;
                     const int v = draw_from_row<DT, CV>(rp, cp, &a_virt, 1, sh.slab_w, ur[2], W);
                     rmass = W * h.iZp;
@@ -280,9 +280,9 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                         if (v < 0) {
                             // no residual mass: fall back to p itself
                             flags |= MDSD_FLAG_ZERO_RESIDUAL;
-                            __syncthreads();
+                            node_barrier();
                             pass_weights_to_slabs<CV>(sp, cp, nullptr, 0, sh.slab_w);
-                            __syncthreads();
+                            node_barrier();
                             float Wp;
                             v = draw_from_row<DT, CV>(rp, cp, nullptr, 0, sh.slab_w, ur[2], Wp);
                             if (rprob) {
@@ -426,7 +426,7 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                     // reject: U <- max(p - (c + Wc rho) q, 0)
                     const float c_new = fmaf(Wc, rho, c);
                     n_rej = i + 1;
-                    if (i > 0) __syncthreads();  // earlier readers of slab_w are done
+                    if (i > 0) node_barrier();  // earlier readers of slab_w are done
                     const float c_iZq = c_new * iZq;
                     const bool want_rem = rem_pending && i == 0;
                     float lane_rem[1] = {0.f};
@@ -449,7 +449,7 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                         block_sum<kWaves, 1>(lane_rem, sh.red, phase);
                         rem_k = lane_rem[0];
                     }
-                    __syncthreads();
+                    node_barrier();
                     const float W_new = slab_total(rp.nslab, [&](int j) { return sh.slab_w[j]; });
                     if (W_new > 0.f) {
                         c = c_new;
@@ -475,7 +475,7 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                     if (slab_c != c || slab_nx != n_rej) {
                         // the slab sums in LDS are not those of the current residual (accepted in
                         // the first round, or a round without mass): rebuild them
-                        __syncthreads();
+                        node_barrier();
                         need_q();
                         for_each2(sp, sq, [&](int s, int chunk, const float(&pa_)[E], const float(&qa_)[E]) {
                             float w[E];
@@ -484,7 +484,7 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
                             if (slab_has_excluded<E>(s, xv, n_rej)) zero_excluded<E>(w, chunk, xv, n_rej);
                             store_slab_sum(sh.slab_w, s, chunk_sum<E>(w));
                         });
-                        __syncthreads();
+                        node_barrier();
                     }
                     auto sv = [&](int j) { return sh.slab_w[j]; };
                     const float W = slab_total(rp.nslab, sv);
@@ -507,17 +507,21 @@ __device__ __forceinline__ NodeOut verify_node(const Params& P, const NodeId& id
 }
 
 template <int DT, bool LOGITS, int METHOD, int NIT>
-__global__ __launch_bounds__(kWG) void verify_kernel(const Params P)
+__global__ __launch_bounds__(kWG * kNodesPerWG) void verify_kernel(const Params P)
 {
-    __shared__ Shared sh;
+    __shared__ Shared shs[kNodesPerWG];
+    Shared& sh = shs[node_slot()];
     int phase = 0;
-    verify_node<DT, LOGITS, METHOD, NIT>(P, node_of_block(P), sh, phase);
+    const NodeId id = node_of_block(P);
+    if (id.b < 0) return;
+    verify_node<DT, LOGITS, METHOD, NIT>(P, id, sh, phase);
 }
 
 template <int DT, bool LOGITS, int METHOD, int NIT>
-__global__ __launch_bounds__(kWG) void verify_path_kernel(const Params P)
+__global__ __launch_bounds__(kWG * kNodesPerWG) void verify_path_kernel(const Params P)
 {
-    __shared__ Shared sh;
+    __shared__ Shared shs[kNodesPerWG];
+    Shared& sh = shs[node_slot()];
     int phase = 0;
     walk_and_verify(P, [&](const NodeId& id) { return verify_node<DT, LOGITS, METHOD, NIT>(P, id, sh, phase); });
 }

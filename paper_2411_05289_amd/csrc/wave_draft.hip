@@ -3,6 +3,7 @@
 #define MDSD_WG 64
 #define MDSD_NS mdsd_wave
 #define MDSD_MAX_SLABS 4
+#define MDSD_NODES_PER_WG 4
 #include "draft_kernel.h"
 
 #include "launch_wave.h"
@@ -14,19 +15,21 @@ static void launch_method(int dtype, bool logits, dim3 grid, hipStream_t st, con
 {
     if (dtype == MDSD_FP32) {
         if (logits)
-            hipLaunchKernelGGL((draft_kernel<0, true, METHOD, 4>), grid, dim3(kWG), 0, st, P);
+            hipLaunchKernelGGL((draft_kernel<0, true, METHOD, 4>), grid, dim3(kWG * kNodesPerWG), 0, st, P);
         else
-            hipLaunchKernelGGL((draft_kernel<0, false, METHOD, 4>), grid, dim3(kWG), 0, st, P);
+            hipLaunchKernelGGL((draft_kernel<0, false, METHOD, 4>), grid, dim3(kWG * kNodesPerWG), 0, st, P);
     } else {
         if (logits)
-            hipLaunchKernelGGL((draft_kernel<1, true, METHOD, 4>), grid, dim3(kWG), 0, st, P);
+            hipLaunchKernelGGL((draft_kernel<1, true, METHOD, 4>), grid, dim3(kWG * kNodesPerWG), 0, st, P);
         else
-            hipLaunchKernelGGL((draft_kernel<1, false, METHOD, 4>), grid, dim3(kWG), 0, st, P);
+            hipLaunchKernelGGL((draft_kernel<1, false, METHOD, 4>), grid, dim3(kWG * kNodesPerWG), 0, st, P);
     }
 }
 
-void launch_draft(int method, int dtype, bool logits, dim3 grid, hipStream_t st, const Params& P)
+void launch_draft(int method, int dtype, bool logits, hipStream_t st, const Params& P)
 {
+    const int64_t items = (int64_t)P.B * P.N;  // one wavefront per node, numbered in one dimension
+    const dim3 grid((unsigned)((items + kNodesPerWG - 1) / kNodesPerWG));
     if (method == kSpecHub)
         launch_method<kSpecHub>(dtype, logits, grid, st, P);
     else if (method == kRRS)

@@ -11,13 +11,55 @@
 namespace MDSD_NS {
 
 constexpr int kWave = 64;
+// A node is handled by kWG threads = kWaves wavefronts.  A workgroup holds kNodesPerWG such groups:
+// more than one only where a group is a single wavefront, so that the groups of a workgroup share
+// nothing and never have to meet at a barrier.
+constexpr int kWG = MDSD_WG;
+constexpr int kWaves = kWG / kWave;
+constexpr int kNodesPerWG = MDSD_NODES_PER_WG;
+static_assert(kNodesPerWG == 1 || kWaves == 1, "several nodes per workgroup: one wavefront each");
 
-// index of this wavefront in its workgroup, as a scalar: the compiler cannot see that
+// index of this wavefront among those of its node, as a scalar: the compiler cannot see that
 // threadIdx.x / 64 is the same in all 64 lanes, and would otherwise guard every per-wave
 // decision with an execution mask instead of a scalar branch
 __device__ __forceinline__ int wave_id()
 {
-    return __builtin_amdgcn_readfirstlane((int)(threadIdx.x / 64u));
+    if constexpr (kWaves == 1) {
+        // 0, in a form the compiler cannot see through: with a constant here it unrolls and
+        // hoists the passes of the one-wavefront build until they need a fifth more registers and run
+        // a fifth slower (RRS on rows of 50 tokens: 240 against 202 us)
+        int zero = 0;
+        asm volatile("" : "+s"(zero));
+        return zero;
+    } else {
+        return __builtin_amdgcn_readfirstlane((int)(threadIdx.x / 64u));
+    }
+}
+// which of the workgroup's nodes this thread works on, and its number among that node's threads
+__device__ __forceinline__ int node_slot()
+{
+    if constexpr (kNodesPerWG == 1)
+        return 0;
+    else
+        return __builtin_amdgcn_readfirstlane((int)(threadIdx.x / 64u));
+}
+__device__ __forceinline__ int node_thread()
+{
+    if constexpr (kNodesPerWG == 1)
+        return (int)threadIdx.x;
+    else
+        return (int)(threadIdx.x & 63u);
+}
+// every thread of the node has arrived and sees the others' writes to LDS.  A single wavefront
+// runs its LDS instructions in order, so there only the compiler has to be kept from moving them.
+__device__ __forceinline__ void node_barrier()
+{
+    if constexpr (kWaves == 1) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    } else {
+        __syncthreads();
+    }
 }
 
 __device__ __forceinline__ float as_f(int v) { return __builtin_bit_cast(float, v); }
@@ -125,7 +167,7 @@ __device__ __forceinline__ void block_sum(float (&v)[NV], BlockScratch<WAVES>& s
         float t = wave_scan_add(v[i]);
         if (lane == 63) s.buf[phase][wave][i] = t;
     }
-    __syncthreads();
+    node_barrier();
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         float t = 0.f;
@@ -146,7 +188,7 @@ __device__ __forceinline__ void block_max(float (&v)[NV], BlockScratch<WAVES>& s
         const float t = wave_max(v[i]);
         if (lane == 63) s.buf[phase][wave][i] = t;
     }
-    __syncthreads();
+    node_barrier();
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         float t = s.buf[phase][0][i];
@@ -165,7 +207,7 @@ __device__ __forceinline__ int block_min_index(int idx, BlockScratch<WAVES>& s, 
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) idx = min(idx, __shfl_xor(idx, off, 64));
     if (lane == 0) s.ibuf[phase][wave] = idx;
-    __syncthreads();
+    node_barrier();
     int r = s.ibuf[phase][0];
 #pragma unroll
     for (int w = 1; w < WAVES; ++w) r = min(r, s.ibuf[phase][w]);

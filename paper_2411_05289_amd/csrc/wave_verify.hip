@@ -3,6 +3,7 @@
 #define MDSD_WG 64
 #define MDSD_NS mdsd_wave
 #define MDSD_MAX_SLABS 4
+#define MDSD_NODES_PER_WG 1
 #include "verify_generic.h"
 
 #include "launch_wave.h"
@@ -13,9 +14,9 @@ template <int DT, bool LG, int METHOD>
 static void launch_one(bool path, dim3 grid, hipStream_t st, const Params& P)
 {
     if (path)
-        hipLaunchKernelGGL((verify_path_kernel<DT, LG, METHOD, 4>), grid, dim3(kWG), 0, st, P);
+        hipLaunchKernelGGL((verify_path_kernel<DT, LG, METHOD, 4>), grid, dim3(kWG * kNodesPerWG), 0, st, P);
     else
-        hipLaunchKernelGGL((verify_kernel<DT, LG, METHOD, 4>), grid, dim3(kWG), 0, st, P);
+        hipLaunchKernelGGL((verify_kernel<DT, LG, METHOD, 4>), grid, dim3(kWG * kNodesPerWG), 0, st, P);
 }
 
 template <int METHOD>
@@ -36,6 +37,7 @@ static void launch_method(int dtype, bool logits, bool path, dim3 grid, hipStrea
 
 void launch_verify(int method, int dtype, bool logits, bool path, dim3 grid, hipStream_t st, const Params& P)
 {
+    static_assert(kNodesPerWG == 1, "the caller's grid has one workgroup per node (path: per tree)");
     if (method == kSpecHub)
         launch_method<kSpecHub>(dtype, logits, path, grid, st, P);
     else if (method == kRRS)
