@@ -3,7 +3,7 @@
 // draft_*.hip; the device code they share is in node_common.h), the tree walk and Philox
 // kernels, and the C entry points.
 #include "launch.h"
-#include "launch_wave.h"
+#include "launch_small.h"
 
 #include <atomic>
 
@@ -132,13 +132,17 @@ static int resident_chunks(const mdsd_problem* pb)
     if (per_lane <= 16) return 16;
     return 0;
 }
-// Vocabularies of a few hundred tokens: one wavefront per node (the 64-thread build of the generic
-// kernels) instead of one 512-thread workgroup, most of whose wavefronts would hold no part of the row
-static bool row_fits_one_wave(const mdsd_problem* pb)
+// Short rows go to a build of the generic kernels with fewer threads per node (1, 2 or 4 wavefronts:
+// four chunks per lane) instead of one 512-thread workgroup most of whose wavefronts would hold no
+// part of the row; 0 = the main build
+static int small_build(const mdsd_problem* pb)
 {
     const int per_chunk = pb->dtype == MDSD_FP32 ? 4 : 8;
     const int64_t nchunk = ((int64_t)pb->V + 2 * per_chunk - 2) / per_chunk;
-    return nchunk <= mdsd_wave::kWaveBuildMaxChunks;
+    if (nchunk <= mdsd_wave::kMaxChunks) return 1;
+    if (nchunk <= mdsd_pair::kMaxChunks) return 2;
+    if (nchunk <= mdsd_quad::kMaxChunks) return 4;
+    return 0;
 }
 // true when some element of some row may need masking: a row that does not start on a
 // 16-byte boundary, or a vocabulary that is not a whole number of 16-byte chunks
@@ -168,9 +172,11 @@ static void launch_verify(int method, const mdsd_problem* pb, const Params& P, b
     const bool lg = pb->kind == MDSD_LOGITS;
     int nit = resident_chunks(pb);
     const dim3 grid = path ? dim3((unsigned)P.B) : node_grid(P, nit), block(kWG);
-    if (row_fits_one_wave(pb)) {
-        mdsd_wave::launch_verify(method, pb->dtype, lg, path, grid, st, P);
-        return;
+    switch (small_build(pb)) {
+    case 1: mdsd_wave::launch_verify(method, pb->dtype, lg, path, grid, st, P); return;
+    case 2: mdsd_pair::launch_verify(method, pb->dtype, lg, path, grid, st, P); return;
+    case 4: mdsd_quad::launch_verify(method, pb->dtype, lg, path, grid, st, P); return;
+    default: break;
     }
     if (method == kSpecHub && lg && nit > 0) {
         launch_spechub_resident(pb->dtype, nit, rows_need_mask(pb), path, grid, block, st, P);
@@ -199,9 +205,11 @@ static void launch_draft(int method, const mdsd_problem* pb, const Params& P, hi
     const bool lg = pb->kind == MDSD_LOGITS;
     const int nit = resident_chunks(pb);
     const dim3 grid = node_grid(P, nit), block(kWG);
-    if (row_fits_one_wave(pb)) {
-        mdsd_wave::launch_draft(method, pb->dtype, lg, st, P);
-        return;
+    switch (small_build(pb)) {
+    case 1: mdsd_wave::launch_draft(method, pb->dtype, lg, st, P); return;
+    case 2: mdsd_pair::launch_draft(method, pb->dtype, lg, st, P); return;
+    case 4: mdsd_quad::launch_draft(method, pb->dtype, lg, st, P); return;
+    default: break;
     }
     const int es = pb->dtype == MDSD_FP32 ? 4 : 2;
     const bool masked = ((uintptr_t)pb->draft & 15) || ((pb->ld_d * es) & 15) || (pb->V % (16 / es));

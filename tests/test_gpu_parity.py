@@ -228,15 +228,25 @@ def test_rows_masked_down_to_a_few_tokens(method, V, K, request):
 # (dtype, kind, V, row offset in elements): between them these reach every instantiation the
 # launchers can choose: rows in registers with 4, 8 or 16 chunks per lane, with and without masked
 # first / last chunks, fp32 and bf16, logits and probabilities, the streamed forms, and the
-# one-wavefront-per-node build that takes rows of up to 256 16-byte chunks.
+# builds for short rows with one, two or four wavefronts per node (rows of up to 256, 512 and
+# 1024 16-byte chunks).
 _VARIANTS = [
     ("fp32", "logits", 1000, 0),     # one wavefront per node: fp32 logits, four chunks per lane
     ("fp32", "logits", 301, 1),      # ... masked
-    ("bf16", "logits", 2040, 0),     # ... bf16 logits, the longest row of that build
+    ("bf16", "logits", 2040, 0),     # ... bf16 logits, the longest aligned row of that build
     ("bf16", "logits", 777, 3),      # ... masked
     ("fp32", "probs", 513, 0),       # ... fp32 probabilities
-    ("bf16", "probs", 2042, 0),      # the shortest row of the 512-thread build: bf16 probabilities
-    ("fp32", "logits", 1021, 0),     # ... fp32 logits
+    ("bf16", "probs", 2042, 0),      # two wavefronts per node: the shortest row, bf16 probabilities
+    ("fp32", "logits", 1023, 0),     # ... fp32 logits, masked
+    ("bf16", "logits", 3000, 0),     # ... bf16 logits
+    ("fp32", "probs", 2044, 0),      # ... the longest aligned fp32 row
+    ("bf16", "logits", 4090, 0),     # four wavefronts per node: the shortest row
+    ("bf16", "logits", 5001, 3),     # ... masked
+    ("bf16", "probs", 8184, 0),      # ... the longest aligned row, bf16 probabilities
+    ("fp32", "logits", 3001, 0),     # ... fp32 logits
+    ("fp32", "probs", 4000, 0),      # ... fp32 probabilities
+    ("bf16", "probs", 8200, 0),      # the 512-thread build again: bf16 probabilities, registers
+    ("fp32", "logits", 4100, 0),     # ... fp32 logits
     ("fp32", "logits", 12000, 0),    # fp32, 8 chunks per lane, no masking
     ("fp32", "logits", 12001, 0),    # ... masked (ld = V is odd: rows start on every 4-byte phase)
     ("fp32", "logits", 30000, 1),    # fp32, 16 chunks per lane, masked (base one element off)
@@ -280,11 +290,12 @@ def test_dispatched_variants(method, dtype, kind, V, off, request):
 
 
 # ----------------------------------------------------------------- general topology
+@pytest.mark.parametrize("V", [2500, 12000])
 @pytest.mark.parametrize("method", ALL)
-def test_unbalanced_tree(method, request):
+def test_unbalanced_tree(method, V, request):
     """first_child given: an unbalanced binary tree (left spine deeper than the right)."""
     fc = [1, 3, -1, 5, -1, 7, -1, -1, -1]      # 0->(1,2) 1->(3,4) 3->(5,6) 5->(7,8)
-    N, k, depth, V, Bn = len(fc), 2, 5, 2500, 12
+    N, k, depth, Bn = len(fc), 2, 5, 12
     t, d = W.llm_like_logits(Bn, N, V, logit_std=3.0, draft_noise_std=1.0, dtype=torch.bfloat16, seed=21, device=DEV)
     wl = W.Workload("unbalanced", Bn, N, V, k, depth, "bf16", "logits", 1.0, 1.0, t, d,
                     first_child=torch.tensor(fc, dtype=torch.int32, device=DEV))
@@ -323,7 +334,7 @@ def test_first_child_entries_that_cannot_be_children_count_as_leaves():
             assert torch.equal(res[0][key], res[1][key]), (bad, key)
 
 
-@pytest.mark.parametrize("V", [600, 4000], ids=["wave_per_node", "workgroup_per_node"])
+@pytest.mark.parametrize("V", [600, 4000, 9000], ids=["one_wave_per_node", "two_waves_per_node", "eight_waves_per_node"])
 @pytest.mark.parametrize("method", ALL)
 def test_trees_of_more_than_64_nodes(method, V, request):
     """127-node trees: the walk (as a launch of its own and inside the verify kernel) goes node
