@@ -24,7 +24,8 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 METRIC = "verified tree nodes/sec and HBM GB/s (% peak) at V=32000, 31-node tree"
-KERNEL_REPS = 200       # launches in each differential event bracket, whatever --steps is
+KERNEL_REPS = 200
+SETTLE_S = 0.1       # launches in each differential event bracket, whatever --steps is
 
 
 def metric_name(wl):
@@ -38,8 +39,8 @@ def metric_name(wl):
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--config", default="3",
                     help="workload configuration 2..5 (3 = the metric's), or `toy`: the toy experiment of "
                          "App. D as a batch (V = 50, T = 0.25, lambda = 0.7; 200 (p, q) pairs x 512 repeats, "
@@ -181,6 +182,16 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    # Set-up, untimed and apart from the W warmup steps: the step is run for SETTLE_S seconds so that
+    # the GPU's clocks are at their working point whatever W is (a timed region that starts within
+    # the first milliseconds of GPU work reads about 2 % slow on this workload: 55.5 against 54.4 us)
+    t_settle = time.perf_counter()
+    i_settle = 0
+    while time.perf_counter() - t_settle < SETTLE_S:
+        for _ in range(50):
+            step(i_settle)
+            i_settle += 1
+        torch.cuda.synchronize()
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -269,6 +280,20 @@ def main():
     event_overhead_ms = one_ms - kernel_ms
     achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
     draft_ms, _ = differential(lambda pl: None, lambda pl: pl.draft(stream))
+    # the other placement of the walk, measured beside the one the step uses: the same verify
+    # kernel without (or with) the walk in it, and the step with three (or two) launches
+    other_launch = (lambda pl: pl.verify(stream)) if fused else (lambda pl: pl.verify_and_walk(stream))
+    other_kernel_ms, _ = differential(lambda pl: pl.draft(stream), other_launch)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for i in range(args.steps):
+        pl = plans[i % copies]
+        pl.draft(stream)
+        other_launch(pl)
+        if fused:
+            pl.walk(stream)
+    torch.cuda.synchronize()
+    other_step_ms = 1e3 * (time.perf_counter() - t1) / args.steps
     es = 2 if wl0.dtype == "bf16" else 4
     draft_bytes = Bn * wl0.n_internal * wl0.V * es
     # Reference line: a plain device copy of the same target rows (the library's copy kernel,
@@ -315,6 +340,7 @@ def main():
                    "launch": "hip graph replay" if graphs else
                              ("two launches (walk inside the verify kernel)" if fused else "three launches"),
                    "input_copies_rotated": copies,
+                   "settle_s_before_warmup": SETTLE_S,
                    "early_exit": True,
                    "draft_stats_handed_to_verify": not args.no_stats,
                    "tokens_per_step_last_batch": tps},
@@ -337,6 +363,11 @@ def main():
                      "plain_copy_reference": {"gbs": plain_copy_gbs, "bytes": copy_bytes,
                                               "what": "device copy of the target rows of one input copy, "
                                                       "bytes read + written"}},
+        "other_walk_placement": {
+            "launch": "three launches (walk as a launch of its own)" if fused else "two launches (walk inside the verify kernel)",
+            "ms_per_step": other_step_ms, "nodes_per_s": Bn * N / (other_step_ms * 1e-3),
+            "verify_kernel_ms": other_kernel_ms,
+            "verify_frac": alg_bytes / (other_kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "other_kernels": {"%s_draft" % args.method: {
             "kernel_ms": draft_ms, "algorithmic_bytes_per_launch": draft_bytes,
             "achieved": draft_bytes / (draft_ms * 1e-3) / 1e9 if draft_ms > 0 else None,

@@ -339,9 +339,10 @@ def tree_walk(pb: Problem, outcome, token, accept_depth=None, emitted=None):
 # itself (two launches per step).  The arrival count keeps a finished workgroup about a
 # microsecond longer on its compute unit, which costs more than the walk's own launch
 # (2-3 us) once a batch is several times what the chip holds at once: measured on one MI355X,
-# 31-node trees at V = 32000: B = 16 27.3 against 29.0 us per step, B = 64 54.9 against 55.6,
-# B = 256 171.1 against 165.6, B = 1024 632 against 605.
-WALK_IN_VERIFY_MAX_NODES = 4096
+# 31-node trees at V = 32000, the two placements timed in turns in one process: B = 16 26.4 against
+# 26.6 us per step, B = 32 36.9 / 37.5, B = 64 54.6 / 54.9, B = 96 73.5 / 73.5, B = 128 91.6 / 91.1,
+# B = 256 171.1 / 166.7, B = 1024 632 / 621.
+WALK_IN_VERIFY_MAX_NODES = 3000
 
 
 class StepPlan:

@@ -558,7 +558,7 @@ def test_step_plan_gives_what_the_separate_calls_give(method):
                 assert torch.equal(out[key], want[key]), (placement, rep, key)
     big = B.Problem.from_workload(W.config(3, device=DEV, B=160, V=1000, seed=1))
     u_d, u_v = uniforms(W.config(3, device=DEV, B=160, V=1000, seed=1), 5)
-    assert B.StepPlan(method, big, u_d, u_v).walk_in_verify is False   # 160 * 31 nodes: beyond the rule
+    assert B.StepPlan(method, big, u_d, u_v).walk_in_verify is False   # 160 * 31 nodes: beyond the rule's 3000
 
 
 # ----------------------------------------------------------------- Monte-Carlo tokens/step
