@@ -197,7 +197,7 @@ __global__ __launch_bounds__(kWG * kNodesPerWG) void draft_kernel(const Params P
                     for (int e = 0; e < E; ++e) w[e] = cq(a[e]);
                     zero_excluded<E>(w, h.slab * 64 + (int)(threadIdx.x & 63), excl, n_excl);
                     v = icdf_in_slab<E>(w, h);
-                    if (v >= 0) remove_token_with(v, h.slab, raw);
+                    if (v >= 0 && i + 1 < k) remove_token_with(v, h.slab, raw);  // the last draw removes nothing
                 }
                 if (v < 0) {
                     v = prev;
@@ -208,8 +208,8 @@ __global__ __launch_bounds__(kWG * kNodesPerWG) void draft_kernel(const Params P
                 if (v < 0) {
                     v = prev;
                     flags |= MDSD_FLAG_Q_EXHAUSTED;
-                } else if (METHOD == kRRSw) {
-                    remove_token(v);
+                } else if (METHOD == kRRSw && i + 1 < k) {
+                    remove_token(v);  // (the last draw removes nothing)
                 }
             }
             prev = v;
