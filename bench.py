@@ -60,8 +60,8 @@ def parse():
                          "itself when the tree's last node is done (the default up to "
                          "binding.WALK_IN_VERIFY_MAX_NODES tree nodes per batch, three launches beyond)")
     ap.add_argument("--graph", action="store_true",
-                    help="replay one HIP graph per step instead of launching its three kernels one by one "
-                         "(measured slower on this workload: 63.9 against 59.8 us per step)")
+                    help="replay one HIP graph per step instead of launching its kernels one by one "
+                         "(measured slower on this workload: 58.8 against 53.8 us per step)")
     ap.add_argument("--no-path-only", action="store_true",
                     help="skip the extra measurement of the path-only step (draft + *_verify_path)")
     ap.add_argument("--calibration-copy", action="store_true",
