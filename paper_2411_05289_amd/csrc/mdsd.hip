@@ -10,14 +10,22 @@
 namespace mdsd {
 
 // ---------------------------------------------------------------- tree walk
-// The walk as a launch of its own: one wavefront per tree (see wave_walk in node_common.h).
+// The walk as a launch of its own (see group_walk and wave_walk in node_common.h).  Trees of at most
+// 64 nodes: a group of W lanes per tree (W = the power of two from N up), 64 / W trees per wavefront.
+// Larger trees (W = 0): one wavefront per tree.
 __global__ __launch_bounds__(256) void tree_walk_kernel(const int32_t* outcome, const int32_t* token, int B, int N,
-                                                        int k, int depth, const int32_t* first_child,
+                                                        int W, int k, int depth, const int32_t* first_child,
                                                         int32_t* accept_depth, int32_t* emitted)
 {
-    const int b = blockIdx.x * (blockDim.x / 64) + (int)(threadIdx.x / 64);
-    if (b >= B) return;
-    wave_walk<false>(outcome, token, b, N, k, depth, first_child, accept_depth, emitted);
+    const int wave = blockIdx.x * (blockDim.x / 64) + (int)(threadIdx.x / 64);
+    if (W == 0) {
+        if (wave < B) wave_walk<false>(outcome, token, wave, N, k, depth, first_child, accept_depth, emitted);
+        return;
+    }
+    const int per_wave = 64 / W;
+    if ((int64_t)wave * per_wave >= B) return;  // the whole wavefront: the shuffles below need every lane of the others
+    const int b = wave * per_wave + (int)(threadIdx.x & 63) / W;
+    group_walk<false>(outcome, token, b < B ? b : 0, b < B, W, N, k, depth, first_child, accept_depth, emitted);
 }
 
 // ---------------------------------------------------------------- Philox4x32-10
@@ -224,9 +232,15 @@ static void launch_draft(int method, const mdsd_problem* pb, const Params& P, hi
 static int walk(const mdsd_problem* pb, const int32_t* outcome, const int32_t* token,
                 int32_t* accept_depth, int32_t* emitted, hipStream_t st)
 {
-    const int trees_per_block = 4;
-    hipLaunchKernelGGL(tree_walk_kernel, dim3((pb->B + trees_per_block - 1) / trees_per_block),
-                       dim3(64 * trees_per_block), 0, st, outcome, token, pb->B, pb->N, pb->k, pb->depth,
+    int W = 0;  // lanes per tree
+    if (pb->N <= 64) {
+        W = 1;
+        while (W < pb->N) W *= 2;
+    }
+    const int64_t waves = W ? ((int64_t)pb->B * W + 63) / 64 : (int64_t)pb->B;
+    const int waves_per_block = 4;
+    hipLaunchKernelGGL(tree_walk_kernel, dim3((unsigned)((waves + waves_per_block - 1) / waves_per_block)),
+                       dim3(64 * waves_per_block), 0, st, outcome, token, pb->B, pb->N, W, pb->k, pb->depth,
                        pb->first_child, accept_depth, emitted);
     return hipGetLastError() == hipSuccess ? MDSD_OK : MDSD_E_LAUNCH;
 }

@@ -137,34 +137,57 @@ __device__ __forceinline__ int load_node_word(const int32_t* p)
         return *p;
 }
 
+// The walk of trees of at most 64 nodes by groups of W lanes (W a power of two, N <= W <= 64):
+// lane l of a group fetches node l of the group's tree b, so the whole tree arrives in one trip to
+// memory and the walk runs on registers; a wavefront walks 64 / W trees side by side.  All 64 lanes
+// are active; tree_ok is false in the lanes of a group that has no tree.
+template <bool COHERENT>
+__device__ __forceinline__ void group_walk(const int32_t* outcome, const int32_t* token, int b, bool tree_ok, int W,
+                                           int N, int k, int depth, const int32_t* first_child,
+                                           int32_t* accept_depth, int32_t* emitted)
+{
+    const int lane = threadIdx.x & 63;
+    const int l = lane & (W - 1), base = lane - l;
+    const bool in_tree = tree_ok && l < N;
+    const int32_t* oc = outcome + (int64_t)b * N;
+    const int32_t* tk = token + (int64_t)b * N;
+    const int o_l = in_tree ? load_node_word<COHERENT>(oc + l) : -1;
+    const int t_l = in_tree ? load_node_word<COHERENT>(tk + l) : -1;
+    const int c_l = in_tree ? walk_first_child(first_child, l, k, N) : -1;
+    int n = 0, d = 0, mine = -1;  // lane d of the group keeps the token emitted at depth d (d < N <= W)
+    bool alive = tree_ok;
+    // the same number of steps in every group (the shuffles need every lane): the longest path
+    const int steps = depth < W ? depth : W;
+    for (int s = 0; s < steps; ++s) {
+        const int t = __shfl(t_l, base + n, 64), o = __shfl(o_l, base + n, 64), c = __shfl(c_l, base + n, 64);
+        if (alive && l == d) mine = t;
+        if (alive && !(c < 0 || o < 0 || o >= k || d + 1 >= depth || d + 1 >= W)) {
+            n = c + o;  // < N: c + k <= N
+            ++d;
+        } else {
+            alive = false;
+        }
+    }
+    if (!tree_ok) return;
+    int32_t* em = emitted + (int64_t)b * depth;
+    for (int i = l; i < depth; i += W) em[i] = i < W ? mine : -1;
+    if (l == 0) accept_depth[b] = d;
+}
+
 // The walk of tree b by one wavefront (all 64 lanes active, the same b in every lane).  Trees of
-// at most 64 nodes: lane n fetches node n, so the whole tree arrives in one trip to memory and
-// the walk runs on registers.  Larger trees: node after node from memory.
+// at most 64 nodes: on registers, as above.  Larger trees: node after node from memory.
 template <bool COHERENT>
 __device__ __forceinline__ void wave_walk(const int32_t* outcome, const int32_t* token, int b, int N, int k,
                                           int depth, const int32_t* first_child, int32_t* accept_depth,
                                           int32_t* emitted)
 {
     const int lane = threadIdx.x & 63;
-    const int32_t* oc = outcome + (int64_t)b * N;
-    const int32_t* tk = token + (int64_t)b * N;
-    int32_t* em = emitted + (int64_t)b * depth;
     if (N <= 64) {
-        const bool in_tree = lane < N;
-        const int o_l = in_tree ? load_node_word<COHERENT>(oc + lane) : -1;
-        const int t_l = in_tree ? load_node_word<COHERENT>(tk + lane) : -1;
-        const int c_l = in_tree ? walk_first_child(first_child, lane, k, N) : -1;
-        int n = 0, d = 0, mine = -1;  // lane d keeps the token emitted at depth d (d < N <= 64)
-        for (;;) {
-            const int t = __shfl(t_l, n, 64), o = __shfl(o_l, n, 64), c = __shfl(c_l, n, 64);
-            if (lane == d) mine = t;
-            if (c < 0 || o < 0 || o >= k || d + 1 >= depth || d + 1 >= 64) break;
-            n = c + o;  // < N: c + k <= N
-            ++d;
-        }
-        for (int i = lane; i < depth; i += 64) em[i] = i < 64 ? mine : -1;
-        if (lane == 0) accept_depth[b] = d;
+        group_walk<COHERENT>(outcome, token, b, true, 64, N, k, depth, first_child, accept_depth, emitted);
     } else {
+        const int32_t* oc = outcome + (int64_t)b * N;
+        const int32_t* tk = token + (int64_t)b * N;
+        int32_t* em = emitted + (int64_t)b * depth;
         if (lane == 0) {
             for (int i = 0; i < depth; ++i) em[i] = -1;
             int n = 0, d = 0;
