@@ -27,8 +27,9 @@ def _case(Bn, V, depth, seed, stats):
 
 @pytest.mark.parametrize("stats", [True, False], ids=["draft_records", "self_contained"])
 def test_static_entry_point_matches_spechub_verify(stats):
-    # first call: 48 trees of 31 nodes, rows in registers; second call: 5 trees of 15 nodes, streamed rows
-    for Bn, V, depth, seed in ((48, 32000, 5, 71), (5, 70016, 4, 72)):
+    # first call: 48 trees of 31 nodes, rows in registers; second call: 5 trees of 15 nodes, streamed
+    # rows; third: 3 trees of 7 nodes, rows short enough for one wavefront per node
+    for Bn, V, depth, seed in ((48, 32000, 5, 71), (5, 70016, 4, 72), (3, 600, 3, 74)):
         pb, tokens, u_v = _case(Bn, V, depth, seed, stats)
         want = B.spechub_verify(pb, tokens, u_v, flags=True, walk=True)              # walk as its own launch
         want_ws = B.spechub_verify(pb, tokens, u_v, workspace=B.alloc_workspace(pb), flags=True, walk=True)
