@@ -1,9 +1,10 @@
-// Device code shared by every kernel family of the library: the parameter block, the LDS
-// layout of a workgroup, the node a workgroup owns, the passes over a row (maximum, argmax,
+// Device code shared by every kernel family of the library: the LDS layout of a node's
+// threads, the node a workgroup owns, the passes over a row (maximum, argmax,
 // weights to slab sums, draws), the element arithmetic of the three methods, the leaf case,
 // the path-only walk and the one-sweep statistics of a streamed row.
 //
-// One workgroup of 512 threads (8 wavefronts) owns one tree node -- or, in the path-only
+// A group of kWG threads (512 = 8 wavefronts in the main build, fewer in the builds for short
+// rows: build_config.h) owns one tree node -- or, in the path-only
 // kernels, one tree, whose visited nodes it handles one after another.  A node's work is a few
 // passes over its target row and, if it has children, its draft row, each pass a sequence of
 // fully coalesced 16-byte loads or a sweep over registers that hold the row:
