@@ -561,6 +561,38 @@ def test_step_plan_gives_what_the_separate_calls_give(method):
     assert B.StepPlan(method, big, u_d, u_v).walk_in_verify is False   # 160 * 31 nodes: beyond the rule's 3000
 
 
+@pytest.mark.parametrize("shape", ["headline", "small_trees", "long_rows"])
+def test_walk_inside_the_verify_kernel_over_many_launches(shape):
+    """The arrival counters hand outcomes from workgroup to workgroup inside one launch; a mistake
+    in that hand-over would show now and then, not every time.  2000 launches back to back on
+    rotating inputs, each compared on the device with what the walk as a launch of its own gave."""
+    if shape == "headline":
+        wls = [W.config(3, device=DEV, seed=s, B=32) for s in range(3)]
+    elif shape == "small_trees":
+        wls = [W.toy_pairs(0.25, 0.7, 200, repeats=4, seed=s, device=DEV) for s in range(3)]
+    else:
+        wls = [W.config(5, device=DEV, seed=s, B=8, k=2, depth=4) for s in range(2)]
+    plans, want = [], []
+    for i, wl in enumerate(wls):
+        pb = B.Problem.from_workload(wl)
+        u_d, u_v = uniforms(wl, i)
+        ref = B.StepPlan("spechub", pb, u_d, u_v, walk_in_verify=False).run()
+        torch.cuda.synchronize()
+        want.append({key: ref[key].clone() for key in ("accept_depth", "emitted", "outcome", "token")})
+        plans.append(B.StepPlan("spechub", pb, u_d, u_v, walk_in_verify=True))
+    bad = torch.zeros((), dtype=torch.int64, device=DEV)
+    for i in range(2000):
+        pl, w = plans[i % len(plans)], want[i % len(plans)]
+        pl.out["accept_depth"].fill_(-7)
+        pl.out["emitted"].fill_(-7)
+        out = pl.run()
+        for key in w:
+            bad += (out[key] != w[key]).sum()
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 0
+    assert not any(bool(pl.workspace.any()) for pl in plans)   # every counter back at zero
+
+
 # ----------------------------------------------------------------- Monte-Carlo tokens/step
 @pytest.mark.parametrize("method", ALL)
 def test_tokens_per_step_within_3_sigma(method, request):
