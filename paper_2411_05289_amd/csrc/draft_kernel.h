@@ -177,6 +177,44 @@ __global__ __launch_bounds__(kWG * kNodesPerWG) void draft_kernel(const Params P
             out_tok[0] = a_virt - rq.head;
             out_tok[1] = v2 - rq.head;
         }
+    } else if constexpr (NIT == 0 && METHOD == kRRS) {
+        // streamed rows, k independent draws from one distribution: the slabs of up to four draws are
+        // found first (slab sums, no memory), their chunks asked for together, and the draws finished as
+        // the chunks arrive -- one trip to memory per four draws instead of one per draw
+        const float W = slab_total(rq.nslab, sv);
+        if (P.stats_out && threadIdx.x == 0) P.stats_out[row] = mdsd_row_stats{mm[0], W, -1, 0};
+        int prev = rq.head;
+        constexpr int kBatch = 4;
+        for (int i0 = 0; i0 < k; i0 += kBatch) {
+            SlabHit h[kBatch];
+            uint4 raw[kBatch];
+            bool found[kBatch];
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                h[j] = SlabHit{0, 0.f, 0.f};
+                found[j] = i0 + j < k && icdf_find_slab(rq.nslab, ur[i0 + j < k ? i0 + j : 0], W, sv, h[j]);
+                raw[j] = fetch_chunk(rq, (found[j] ? h[j].slab : 0) * 64 + (int)(threadIdx.x & 63));
+            }
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                if (i0 + j < k) {
+                    int v = -1;
+                    if (found[j]) {
+                        float a[E], w[E];
+                        finish_chunk<DT>(rq, h[j].slab * 64 + (int)(threadIdx.x & 63), raw[j], CV::fill(), a);
+#pragma unroll
+                        for (int e = 0; e < E; ++e) w[e] = cq(a[e]);
+                        v = icdf_in_slab<E>(w, h[j]);
+                    }
+                    if (v < 0) {
+                        v = prev;
+                        flags |= MDSD_FLAG_Q_EXHAUSTED;
+                    }
+                    prev = v;
+                    out_tok[i0 + j] = v - rq.head;
+                }
+            }
+        }
     } else {
         int prev = rq.head;
         for (int i = 0; i < k; ++i) {
