@@ -159,7 +159,9 @@ typedef struct mdsd_result {
  * rrsw_verify put a non-NULL workspace to use when they are also asked for the walk
  * (out->accept_depth and out->emitted): it holds one int32 arrival counter per tree, with which
  * the verify kernel walks each tree itself as soon as the tree's last node is done, instead of
- * running the walk as a second launch behind it (same results; one launch less per step).
+ * running the walk as a second launch behind it (same results; one launch less per step, which
+ * pays for batches of up to about 3000 tree nodes: beyond that the counting costs more than the
+ * launch it saves, and ws = NULL is the faster call).
  *   - mdsd_workspace_bytes(pb) = 4 * pb->B bytes; ws must be 4-byte aligned device memory;
  *     a smaller ws_bytes is MDSD_E_WORKSPACE.
  *   - The counters must be ZERO when the call starts.  Every call leaves them zero again, so a
