@@ -42,7 +42,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--config", default="3",
-                    help="workload configuration 2..5 (3 = the metric's), or `toy`: the toy experiment of "
+                    help="workload configuration 1..5 (3 = the metric's), or `toy`: the toy experiment of "
                          "App. D as a batch (V = 50, T = 0.25, lambda = 0.7; 200 (p, q) pairs x 512 repeats, "
                          "one draft step each), reported in pairs/s")
     ap.add_argument("--method", default="spechub", choices=["spechub", "rrs", "rrsw"])
