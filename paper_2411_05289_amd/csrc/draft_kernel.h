@@ -177,12 +177,41 @@ __global__ __launch_bounds__(kWG * kNodesPerWG) void draft_kernel(const Params P
             out_tok[0] = a_virt - rq.head;
             out_tok[1] = v2 - rq.head;
         }
+    } else if constexpr (NIT > 0 && METHOD == kRRS && kWaves > 1) {
+        // rows in registers, k independent draws from one distribution: every wave finds the slab of
+        // every draw, the wave that owns a drawn slab searches it, and all k results cross through
+        // LDS behind one barrier instead of one barrier per draw (a node with a single wavefront has
+        // no barriers to save and takes the plain loop below)
+        const float W = slab_total(rq.nslab, sv);
+        if (P.stats_out && node_thread() == 0) P.stats_out[row] = mdsd_row_stats{mm[0], W, -1, 0};
+        for (int i = 0; i < k; ++i) {
+            SlabHit h{-1, 0.f, 0.f};
+            const bool found = icdf_find_slab(rq.nslab, ur[i], W, sv, h);  // the same in every wave
+            if (found && wave_id() == h.slab % kWaves) {
+                float w[E];
+                cw_reg(h.slab / kWaves, w);
+                const int v = icdf_in_slab<E>(w, h);
+                if ((threadIdx.x & 63) == 0) sh.node_x[i] = v;
+            }
+            if (!found && node_thread() == 0) sh.node_x[i] = -1;
+        }
+        node_barrier();
+        int prev = rq.head;
+        for (int i = 0; i < k; ++i) {
+            int v = sh.node_x[i];
+            if (v < 0) {
+                v = prev;
+                flags |= MDSD_FLAG_Q_EXHAUSTED;
+            }
+            prev = v;
+            out_tok[i] = v - rq.head;
+        }
     } else if constexpr (NIT == 0 && METHOD == kRRS) {
         // streamed rows, k independent draws from one distribution: the slabs of up to four draws are
         // found first (slab sums, no memory), their chunks asked for together, and the draws finished as
         // the chunks arrive -- one trip to memory per four draws instead of one per draw
         const float W = slab_total(rq.nslab, sv);
-        if (P.stats_out && threadIdx.x == 0) P.stats_out[row] = mdsd_row_stats{mm[0], W, -1, 0};
+        if (P.stats_out && node_thread() == 0) P.stats_out[row] = mdsd_row_stats{mm[0], W, -1, 0};
         int prev = rq.head;
         constexpr int kBatch = 4;
         for (int i0 = 0; i0 < k; i0 += kBatch) {
