@@ -3,6 +3,7 @@
 // draft_*.hip; the device code they share is in node_common.h), the tree walk and Philox
 // kernels, and the C entry points.
 #include "launch.h"
+#include "launch_half.h"
 #include "launch_small.h"
 
 #include <atomic>
@@ -174,6 +175,9 @@ static dim3 node_grid(const Params& P, int nit)
     return dim3((unsigned)(P.B * P.N));
 }
 
+// tree nodes per batch from which the 256-thread verify kernels take over from the 512-thread ones
+constexpr int64_t kHalfWidthMinNodes = 2300;
+
 // path == false: one workgroup per node.  path == true: one workgroup per tree.
 static void launch_verify(int method, const mdsd_problem* pb, const Params& P, bool path, hipStream_t st)
 {
@@ -185,6 +189,20 @@ static void launch_verify(int method, const mdsd_problem* pb, const Params& P, b
     case 2: mdsd_pair::launch_verify(method, pb->dtype, lg, path, grid, st, P); return;
     case 4: mdsd_quad::launch_verify(method, pb->dtype, lg, path, grid, st, P); return;
     default: break;
+    }
+    // Rows of eight chunks per lane, the draft call's records at hand, and a batch that fills the chip
+    // several times over: 256 threads per node with sixteen chunks per lane, four nodes per CU
+    // instead of three (config-3 rows, 31 nodes per tree: B = 80 41.8 -> 41.1 us, B = 128 58.7 -> 56.6 us,
+    // B = 1024 437 -> 410 us; B = 64 33.3 -> 34.3 us and B = 32 21.5 -> 23.5 us, hence the bound)
+    const bool half_width = lg && nit == 8 && !path && P.stats_in != nullptr &&
+                            (int64_t)P.B * P.N >= kHalfWidthMinNodes;
+    if (half_width && method == kSpecHub) {
+        mdsd_half::launch_spechub(pb->dtype, rows_need_mask(pb), grid, st, P);
+        return;
+    }
+    if (half_width && method != kSpecHub && mdsd_half::rrs_covers(pb->dtype, rows_need_mask(pb))) {
+        mdsd_half::launch_rrs(method == kRRSw, pb->dtype, rows_need_mask(pb), grid, st, P);
+        return;
     }
     if (method == kSpecHub && lg && nit > 0) {
         launch_spechub_resident(pb->dtype, nit, rows_need_mask(pb), path, grid, block, st, P);

@@ -289,6 +289,37 @@ def test_dispatched_variants(method, dtype, kind, V, off, request):
     note(request, check_case(method, wl, seed=V % 1000, full_outputs=V <= 20001))
 
 
+# ----------------------------------------------------------------- large batches
+_LARGE = [
+    ("bf16", 32000, 0),     # the headline row: 256 threads per node, sixteen chunks per lane
+    ("bf16", 20001, 0),     # ... masked (RRS / RRSw: the generic kernel)
+    ("fp32", 12000, 0),     # fp32
+    ("fp32", 12001, 1),     # ... masked
+]
+
+
+@pytest.mark.parametrize("method", ALL)
+@pytest.mark.parametrize("dtype,V,off", _LARGE, ids=["%s_V%d_off%d" % v for v in _LARGE])
+def test_batches_of_more_than_2300_nodes(method, dtype, V, off, request):
+    """From 2300 tree nodes per batch the verify calls that have the draft call's records run their
+    rows of eight chunks per lane on 256-thread kernels; sampled sequences against the oracle."""
+    k, depth = (2, 3) if method == "spechub" else (3, 2)
+    N = W.tree_nodes(k, depth)
+    Bn = 2300 // N + 3
+    td = torch.float32 if dtype == "fp32" else torch.bfloat16
+    t, d = W.llm_like_logits(Bn, N, V, logit_std=3.0, draft_noise_std=1.5, dtype=td, seed=V + 1, device=DEV)
+    if off:
+        big_t = torch.zeros((Bn * N * V + off,), dtype=td, device=DEV)
+        big_d = torch.zeros((Bn * N * V + off,), dtype=td, device=DEV)
+        tv, dv = big_t[off:].view(Bn, N, V), big_d[off:].view(Bn, N, V)
+        tv.copy_(t)
+        dv.copy_(d)
+        t, d = tv, dv
+    wl = W.Workload("large_%s_V%d" % (dtype, V), Bn, N, V, k, depth, dtype, "logits", 0.9, 1.1, t, d)
+    assert wl.B * wl.N >= 2300
+    note(request, check_case(method, wl, seed=V % 1000, seqs=[0, 1, Bn // 2, Bn - 1], full_outputs=False))
+
+
 # ----------------------------------------------------------------- general topology
 @pytest.mark.parametrize("V", [2500, 12000])
 @pytest.mark.parametrize("method", ALL)
