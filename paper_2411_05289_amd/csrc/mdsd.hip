@@ -229,7 +229,12 @@ static void launch_verify(int method, const mdsd_problem* pb, const Params& P, b
 static void launch_draft(int method, const mdsd_problem* pb, const Params& P, hipStream_t st)
 {
     const bool lg = pb->kind == MDSD_LOGITS;
-    const int nit = resident_chunks(pb);
+    int nit = resident_chunks(pb);
+    // Rows of sixteen chunks per lane are streamed: the draft kernel with such a row in registers
+    // fits two workgroups on a CU, the streaming one four, and its one-sweep statistics are the
+    // cheaper (V = 50304, B = 64: spechub_draft 33.7 -> 24.7 us, rrsw_draft 47.2 -> 26.8 us).  At
+    // eight chunks per lane the row in registers wins (V = 32000: 18.8 against 19.4 us).
+    if (nit == 16 && lg) nit = 0;  // (rows of probabilities have no one-sweep form and stay in registers)
     const dim3 grid = node_grid(P, nit), block(kWG);
     switch (small_build(pb)) {
     case 1: mdsd_wave::launch_draft(method, pb->dtype, lg, st, P); return;

@@ -3,12 +3,11 @@
 
 namespace mdsd {
 
-// which shapes the RRS kernel for rows in registers is built for (the others would spill or run
-// one workgroup per CU; they take the generic kernel): fp32 in every size, bf16 up to 8 chunks per
-// lane and only for rows that need no masking
+// which shapes the RRS kernel for rows in registers is built for (the others would spill; they
+// take the generic kernel): fp32 in every size, bf16 only for rows that need no masking
 bool rrs_resident_covers(int dtype, int nit, bool masked)
 {
-    return nit > 0 && (dtype == MDSD_FP32 || (nit <= 8 && !masked));
+    return nit > 0 && (dtype == MDSD_FP32 || !masked);
 }
 template <bool WO>
 static void launch_rrs_resident_of(int dtype, int nit, bool masked, dim3 grid, dim3 block, hipStream_t st,
@@ -24,7 +23,12 @@ static void launch_rrs_resident_of(int dtype, int nit, bool masked, dim3 grid, d
             if (masked) MDSD_LAUNCH_RRS(0, 16, true); else MDSD_LAUNCH_RRS(0, 16, false);
         }
     } else {
-        if (nit == 4) MDSD_LAUNCH_RRS(1, 4, false); else MDSD_LAUNCH_RRS(1, 8, false);
+        if (nit == 4)
+            MDSD_LAUNCH_RRS(1, 4, false);
+        else if (nit == 8)
+            MDSD_LAUNCH_RRS(1, 8, false);
+        else
+            MDSD_LAUNCH_RRS(1, 16, false);
     }
 #undef MDSD_LAUNCH_RRS
 }

@@ -264,7 +264,7 @@ __device__ __forceinline__ NodeOut rrs_node_resident(const Params& P, const Node
 }
 
 template <int DT, int NIT, bool MASKED, bool WO>
-__global__ __launch_bounds__(kWG, (kWG == 256 ? 4 : (NIT <= 8 ? kStatsWavesPerSimd : 2))) void rrs_verify_resident(const Params P)
+__global__ __launch_bounds__(kWG, (kWG == 256 || NIT > 8 ? 4 : kStatsWavesPerSimd)) void rrs_verify_resident(const Params P)
 {
     __shared__ Shared sh;
     __shared__ uint4 q_kept[kDraftChunksKept<NIT>][kWG];

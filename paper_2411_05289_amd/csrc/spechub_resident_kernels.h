@@ -10,7 +10,7 @@ namespace MDSD_NS {
 // (80 registers, three workgroups per CU), without them 4, with 16 chunks per lane 2.  256 threads
 // per node (16 chunks per lane, records at hand): 4 = 128 registers = four nodes per CU.
 template <int NIT, bool STATS>
-constexpr int kVerifyWavesPerSimd = kWG == 256 ? (STATS ? 4 : 2) : (NIT <= 8 ? (STATS ? kStatsWavesPerSimd : 4) : 2);
+constexpr int kVerifyWavesPerSimd = kWG == 256 ? (STATS ? 4 : 2) : (NIT <= 8 ? (STATS ? kStatsWavesPerSimd : 4) : (STATS ? 4 : 2));
 
 // the scalars of one node that come from memory: the pair, the stored logits at its tokens,
 // the uniforms.  Asked for together with the rows, used after the first passes.
